@@ -1,0 +1,173 @@
+/*
+ * roast.h -- C-ABI of the MI355X (gfx950) ROAST hashing hot path.
+ *
+ * ROAST (arXiv 2207.10702) keeps every learnable parameter of a model in one small flat array M
+ * and recovers weights from it block by block: a ROAST-MM layer's virtual weight matrix W (H x O)
+ * is cut into Z1 x Z2 tiles, tile (x, y) is the contiguous, row-major slice of M that starts at a
+ * hashed offset, times a hashed +-1 sign and a per-module scale lambda (Section 3.1, "Matrix
+ * multiplication" paragraph and Algorithm 1); an embedding row is recovered the same way in 1-D
+ * chunks of Z scalars (Section 3.1, "Lookup" paragraph).  W is never materialised.
+ *
+ * Conventions shared by every entry point
+ *   - Pointers named X, Y, dY, dX, M, dM, out, dOut, rows, table_ids, ws are DEVICE pointers owned
+ *     by the caller.  roast_tile_index alone takes HOST pointers.  The library never allocates,
+ *     frees or keeps device memory; scratch comes in through `ws`.
+ *   - `stream` is a hipStream_t (NULL = the default stream).  Calls enqueue work and return; they
+ *     never synchronise.  Outputs are valid once the stream reaches that point.
+ *   - Matrices are row-major with a leading dimension in elements (ld >= number of columns).
+ *   - M and dM are always fp32.  roast_dtype is the type of the activations X / Y / dY / dX;
+ *     products are accumulated in fp32.  With ROAST_BF16 the recovered tile sign*M is rounded to
+ *     bfloat16 (nearest even) when it is staged as the MFMA weight operand and lambda is applied to
+ *     the fp32 accumulator.
+ *   - dM is ACCUMULATED INTO (dM += ...): all layers sharing one M add into one gradient buffer
+ *     (global memory sharing, Section 3.2; gradient equation of Section 3.3).  The caller zeroes it.
+ *   - M is never written.  No entry point touches memory outside the extents stated below.
+ *   - Errors are return codes; nothing is launched when a call returns non-zero, except
+ *     ROAST_ERR_HIP which reports a launch failure from the runtime.
+ *   - Sizes of zero rows (I == 0, N == 0) are a successful no-op.
+ */
+#ifndef ROAST_H
+#define ROAST_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ROAST_OK = 0,
+  ROAST_ERR_ARG = 1,         /* null pointer, negative size, ld too small, bad enum              */
+  ROAST_ERR_SHAPE = 2,       /* H, O, Z1, Z2, D or Z not positive                                */
+  ROAST_ERR_RANGE = 3,       /* a block does not fit (|M| < Z1*Z2 or |M| < Z), or bad hash params */
+  ROAST_ERR_WORKSPACE = 4,   /* ws is null or smaller than the *_workspace query says            */
+  ROAST_ERR_HIP = 5,         /* the HIP runtime refused a launch                                 */
+  ROAST_ERR_UNSUPPORTED = 6  /* combination not implemented                                      */
+} roast_status;
+
+typedef enum { ROAST_F32 = 0, ROAST_BF16 = 1 } roast_dtype;
+
+/* How colliding contributions to one slot of dM are summed.
+ * ATOMIC: fp32 atomic adds, order varies from run to run.
+ * DETERMINISTIC: per-block products go to the workspace and every slot is then summed in a fixed
+ * order; the result is bit-identical from run to run. */
+typedef enum { ROAST_REDUCE_ATOMIC = 0, ROAST_REDUCE_DETERMINISTIC = 1 } roast_reduce_mode;
+
+/*
+ * Hash parameters.  The paper asks only for "a universal hash function" h1 / h2 with range
+ * {0, ..., |M| - block} and an independent sign hash g (Section 3.1); this library uses the
+ * Carter-Wegman multiply-add family over a prime P on the 3-part key (k0, k1, k2):
+ *
+ *     u      = ((a0*(k0 mod P)) mod P + (a1*(k1 mod P)) mod P + (a2*(k2 mod P)) mod P + a3) mod P
+ *     offset = align * (u mod (floor((|M| - block) / align) + 1))
+ *     v      = the same form with s0..s3
+ *     sign   = use_sign ? 1 - 2*(v & 1) : +1
+ *
+ * ROAST-MM keys: (layer_id, x, y) with x the tile row (along H) and y the tile column (along O),
+ * block = Z1*Z2.  Lookup keys: (table_id, row, chunk), block = Z.  "Each module uses independent
+ * hash functions" (Section 3.1) is obtained by giving each module its own k0.
+ * Requirements: 2 <= P < 2^32, every coefficient < P, align >= 1; otherwise ROAST_ERR_RANGE.
+ */
+typedef struct {
+  uint64_t P;
+  uint64_t a0, a1, a2, a3;
+  uint64_t s0, s1, s2, s3;
+  uint32_t use_sign;
+  uint32_t align;
+} roast_hash;
+
+/* One ROAST-MM layer: virtual W is H x O (fan-in x fan-out) in Z1 x Z2 tiles; the tile grid is
+ * ceil(H/Z1) x ceil(O/Z2); edge tiles keep the full Z2 row stride and the full offset range, their
+ * elements outside H x O are never referenced.
+ *   W[i, j] = lambda * sign(x, y) * M[offset(x, y) + Z2*(i mod Z1) + (j mod Z2)],  x = i/Z1, y = j/Z2
+ * m_size is |M| in scalars. */
+typedef struct {
+  int64_t H, O;
+  int32_t Z1, Z2;
+  int64_t m_size;
+  uint32_t layer_id;
+  float lambda;
+  roast_hash hash;
+} roast_mm_desc;
+
+/* One lookup module: rows of D scalars recovered in chunks of Z (the last chunk of a row is short
+ * when Z does not divide D, but is still hashed into {0..|M|-Z}); chunks never straddle rows.
+ *   out[n, i] = lambda * sign(t, r, c) * M[offset(t, r, c) + (i mod Z)],  c = i/Z, r = rows[n], t = table_ids[n] */
+typedef struct {
+  int64_t D;
+  int32_t Z;
+  int64_t m_size;
+  float lambda;
+  roast_hash hash;
+} roast_embed_desc;
+
+/* Human-readable name of a status code (static storage). */
+const char* roast_status_string(roast_status s);
+
+/*
+ * Tile -> (offset, sign) map of one layer: the hash h2 and sign g of Section 3.1 evaluated on the
+ * whole ceil(H/Z1) x ceil(O/Z2) grid, on the HOST with the same integer code the kernels use.
+ * off_host / sgn_host: HOST arrays of ntx*nty entries, row-major in (x, y); either may be NULL.
+ */
+roast_status roast_tile_index(const roast_mm_desc* d, int64_t* off_host, int8_t* sgn_host);
+
+/* The same map computed by the device code path, one thread per tile, into DEVICE arrays
+ * (used to prove that host and device integer code agree bit for bit). */
+roast_status roast_tile_index_device(const roast_mm_desc* d, int64_t* off_dev, int8_t* sgn_dev, void* stream);
+
+/* Chunk -> (offset, sign) of N lookups on the device: off_dev / sgn_dev hold N*ceil(D/Z) entries,
+ * entry n*ceil(D/Z) + c for chunk c of lookup n (the hash h1 of Section 3.1). */
+roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                                      const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream);
+
+/*
+ * ROAST-MM forward, Algorithm 1:  Y[I x O] = X[I x H] * W,  W recovered tile by tile from M.
+ * X: I x H (ldx), Y: I x O (ldy), both of type `dt`; M: m_size fp32.  Y is overwritten.
+ */
+roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I,
+                          const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy, void* stream);
+
+/*
+ * Gradient w.r.t. the input (Section 3.3):  dX[I x H] = dY[I x O] * W^T, W recovered from M.
+ * dX is overwritten.
+ */
+roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I,
+                             const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx, void* stream);
+
+/* Bytes of workspace roast_mm_bwd_dM needs for these sizes and mode (0 = none needed). */
+size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode);
+
+/*
+ * Gradient w.r.t. the shared array (Section 3.3 gradient equation, Appendix A.1):
+ *   dM[offset(x,y) + Z2*o1 + o2] += lambda * sign(x,y) * sum_i X[i, x*Z1+o1] * dY[i, y*Z2+o2]
+ * for every element of every tile; colliding tiles add up.  dM: m_size fp32, accumulated into.
+ * ws / ws_bytes: device scratch of at least roast_mm_bwd_dM_workspace() bytes (may be NULL / 0
+ * when that is 0); its contents on return are unspecified.
+ */
+roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I,
+                             const void* X, int64_t ldx, const void* dY, int64_t ldy,
+                             float* dM, roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Lookup L(l, W) of Section 3.1 for N ids at once: out[N x D] fp32 (dense, row stride D),
+ * rows: N int64 row ids (>= 0), table_ids: N uint32 (first hash key of each lookup).
+ */
+roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                             const uint32_t* table_ids, const float* M, float* out, void* stream);
+
+/* Bytes of workspace roast_embed_bwd needs (0 = none). */
+size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_reduce_mode mode);
+
+/*
+ * Gradient of the lookup (Section 3.3):  dM[offset(t,r,c) + o] += lambda * sign * dOut[n, c*Z + o].
+ * dOut: N x D fp32 (row stride D); dM: m_size fp32, accumulated into.
+ */
+roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                             const uint32_t* table_ids, const float* dOut, float* dM,
+                             roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ROAST_H */

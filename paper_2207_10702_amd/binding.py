@@ -1,0 +1,252 @@
+"""Python names for the C-ABI of libroast_hip.so (see include/roast.h).
+
+Argument marshalling only: every function checks dtypes / contiguity, passes raw device pointers
+and the current HIP stream to the library, and raises RoastError on a non-zero status.  There is no
+fallback: if the library has not been built, loading fails.
+"""
+import ctypes as C
+import os
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libroast_hip.so")
+
+ROAST_F32, ROAST_BF16 = 0, 1
+ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
+
+EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
+           "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
+           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd"]
+
+
+class RoastError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+
+
+class RoastHash(C.Structure):
+    _fields_ = [("P", C.c_uint64),
+                ("a0", C.c_uint64), ("a1", C.c_uint64), ("a2", C.c_uint64), ("a3", C.c_uint64),
+                ("s0", C.c_uint64), ("s1", C.c_uint64), ("s2", C.c_uint64), ("s3", C.c_uint64),
+                ("use_sign", C.c_uint32), ("align", C.c_uint32)]
+
+
+class RoastMMDesc(C.Structure):
+    _fields_ = [("H", C.c_int64), ("O", C.c_int64), ("Z1", C.c_int32), ("Z2", C.c_int32),
+                ("m_size", C.c_int64), ("layer_id", C.c_uint32), ("lam", C.c_float), ("hash", RoastHash)]
+
+
+class RoastEmbedDesc(C.Structure):
+    _fields_ = [("D", C.c_int64), ("Z", C.c_int32), ("m_size", C.c_int64), ("lam", C.c_float),
+                ("hash", RoastHash)]
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load the in-tree library (building it first only if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build()
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+    MP, EP = C.POINTER(RoastMMDesc), C.POINTER(RoastEmbedDesc)
+    lib.roast_status_string.argtypes = [i32]
+    lib.roast_status_string.restype = C.c_char_p
+    lib.roast_tile_index.argtypes = [MP, vp, vp]
+    lib.roast_tile_index_device.argtypes = [MP, vp, vp, vp]
+    lib.roast_chunk_index_device.argtypes = [EP, i64, vp, vp, vp, vp, vp]
+    lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, i64, vp]
+    lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, i64, vp]
+    lib.roast_mm_bwd_dM_workspace.argtypes = [MP, i64, i32]
+    lib.roast_mm_bwd_dM_workspace.restype = sz
+    lib.roast_mm_bwd_dM.argtypes = [MP, i32, i64, vp, i64, vp, i64, vp, i32, vp, sz, vp]
+    lib.roast_embed_fwd.argtypes = [EP, i64, vp, vp, vp, vp, vp]
+    lib.roast_embed_bwd_workspace.argtypes = [EP, i64, i32]
+    lib.roast_embed_bwd_workspace.restype = sz
+    lib.roast_embed_bwd.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp, sz, vp]
+    for name in EXPORTS:
+        f = getattr(lib, name)
+        if name not in ("roast_status_string", "roast_mm_bwd_dM_workspace", "roast_embed_bwd_workspace"):
+            f.restype = i32
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().roast_status_string(int(status)).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise RoastError(status, what)
+
+
+def make_hash(h: Dict[str, int]) -> RoastHash:
+    return RoastHash(*(int(h[k]) for k in ("P", "a0", "a1", "a2", "a3", "s0", "s1", "s2", "s3", "use_sign", "align")))
+
+
+def mm_desc(H: int, O: int, Z1: int, Z2: int, m_size: int, layer_id: int, lam: float, h: Dict[str, int]) -> RoastMMDesc:
+    return RoastMMDesc(int(H), int(O), int(Z1), int(Z2), int(m_size), int(layer_id), float(lam), make_hash(h))
+
+
+def embed_desc(D: int, Z: int, m_size: int, lam: float, h: Dict[str, int]) -> RoastEmbedDesc:
+    return RoastEmbedDesc(int(D), int(Z), int(m_size), float(lam), make_hash(h))
+
+
+# ----------------------------------------------------------------------------- tensor plumbing
+def _torch():
+    import torch
+    return torch
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return int(_torch().cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def _dtype_code(t) -> int:
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return ROAST_F32
+    if t.dtype == torch.bfloat16:
+        return ROAST_BF16
+    raise TypeError(f"activations must be float32 or bfloat16, got {t.dtype}")
+
+
+def _mat(t, name: str) -> Tuple[int, int]:
+    """Device pointer and leading dimension of a 2-D row-major (possibly row-strided) tensor."""
+    if not t.is_cuda or t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be a 2-D device tensor with unit column stride")
+    return t.data_ptr(), (t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0)))
+
+
+def _vec(t, dtype, name: str) -> int:
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor of {dtype}")
+    return t.data_ptr()
+
+
+# ----------------------------------------------------------------------------- entry points
+def roast_tile_index(desc: RoastMMDesc) -> Tuple[np.ndarray, np.ndarray]:
+    """Host evaluation of the tile -> (offset, sign) map; arrays are row-major over (x, y)."""
+    ntx, nty = -(-desc.H // desc.Z1), -(-desc.O // desc.Z2)
+    off = np.empty(max(ntx * nty, 0), dtype=np.int64)
+    sgn = np.empty(max(ntx * nty, 0), dtype=np.int8)
+    _check(load().roast_tile_index(C.byref(desc), off.ctypes.data, sgn.ctypes.data), "roast_tile_index")
+    return off, sgn
+
+
+def roast_tile_index_device(desc: RoastMMDesc, stream=None):
+    torch = _torch()
+    ntx, nty = -(-desc.H // desc.Z1), -(-desc.O // desc.Z2)
+    off = torch.empty(ntx * nty, dtype=torch.int64, device="cuda")
+    sgn = torch.empty(ntx * nty, dtype=torch.int8, device="cuda")
+    _check(load().roast_tile_index_device(C.byref(desc), off.data_ptr(), sgn.data_ptr(), _stream(stream)),
+           "roast_tile_index_device")
+    return off, sgn
+
+
+def roast_chunk_index_device(desc: RoastEmbedDesc, rows, table_ids, stream=None):
+    torch = _torch()
+    N = rows.numel()
+    chunks = -(-desc.D // desc.Z)
+    off = torch.empty(N * chunks, dtype=torch.int64, device="cuda")
+    sgn = torch.empty(N * chunks, dtype=torch.int8, device="cuda")
+    _check(load().roast_chunk_index_device(C.byref(desc), N, _vec(rows, torch.int64, "rows"),
+                                           _vec(table_ids, torch.int32, "table_ids"), off.data_ptr(),
+                                           sgn.data_ptr(), _stream(stream)), "roast_chunk_index_device")
+    return off, sgn
+
+
+def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None):
+    torch = _torch()
+    I = X.shape[0]
+    if X.shape[1] != desc.H:
+        raise ValueError("X must be I x H")
+    if Y is None:
+        Y = torch.empty((I, desc.O), dtype=X.dtype, device=X.device)
+    if Y.dtype != X.dtype or tuple(Y.shape) != (I, desc.O):
+        raise ValueError("Y must be I x O with X's dtype")
+    xp, ldx = _mat(X, "X")
+    yp, ldy = _mat(Y, "Y")
+    _check(load().roast_mm_fwd(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"), yp, ldy,
+                               _stream(stream)), "roast_mm_fwd")
+    return Y
+
+
+def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None):
+    torch = _torch()
+    I = dY.shape[0]
+    if dY.shape[1] != desc.O:
+        raise ValueError("dY must be I x O")
+    if dX is None:
+        dX = torch.empty((I, desc.H), dtype=dY.dtype, device=dY.device)
+    if dX.dtype != dY.dtype or tuple(dX.shape) != (I, desc.H):
+        raise ValueError("dX must be I x H with dY's dtype")
+    gp, ldy = _mat(dY, "dY")
+    xp, ldx = _mat(dX, "dX")
+    _check(load().roast_mm_bwd_dx(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"), xp, ldx,
+                                  _stream(stream)), "roast_mm_bwd_dx")
+    return dX
+
+
+def roast_mm_bwd_dM_workspace(desc: RoastMMDesc, I: int, mode: int = ROAST_REDUCE_ATOMIC) -> int:
+    return int(load().roast_mm_bwd_dM_workspace(C.byref(desc), int(I), int(mode)))
+
+
+def roast_mm_bwd_dM(desc: RoastMMDesc, X, dY, dM, mode: int = ROAST_REDUCE_ATOMIC, ws=None, stream=None):
+    """dM += gradient of this layer.  `ws` is a uint8 device tensor of at least
+    roast_mm_bwd_dM_workspace(...) bytes (only the deterministic mode needs one)."""
+    torch = _torch()
+    I = X.shape[0]
+    if X.shape[1] != desc.H or tuple(dY.shape) != (I, desc.O) or X.dtype != dY.dtype:
+        raise ValueError("X must be I x H and dY I x O, same dtype")
+    if dM.numel() != desc.m_size:
+        raise ValueError("dM must have m_size entries")
+    xp, ldx = _mat(X, "X")
+    gp, ldy = _mat(dY, "dY")
+    wp, wb = (0, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+    _check(load().roast_mm_bwd_dM(C.byref(desc), _dtype_code(X), I, xp, ldx, gp, ldy,
+                                  _vec(dM, torch.float32, "dM"), int(mode), wp, wb, _stream(stream)),
+           "roast_mm_bwd_dM")
+    return dM
+
+
+def roast_embed_fwd(desc: RoastEmbedDesc, rows, table_ids, M, out=None, stream=None):
+    torch = _torch()
+    N = rows.numel()
+    if out is None:
+        out = torch.empty((N, desc.D), dtype=torch.float32, device=rows.device)
+    if tuple(out.shape) != (N, desc.D):
+        raise ValueError("out must be N x D")
+    _check(load().roast_embed_fwd(C.byref(desc), N, _vec(rows, torch.int64, "rows"),
+                                  _vec(table_ids, torch.int32, "table_ids"), _vec(M, torch.float32, "M"),
+                                  _vec(out, torch.float32, "out"), _stream(stream)), "roast_embed_fwd")
+    return out
+
+
+def roast_embed_bwd_workspace(desc: RoastEmbedDesc, N: int, mode: int = ROAST_REDUCE_ATOMIC) -> int:
+    return int(load().roast_embed_bwd_workspace(C.byref(desc), int(N), int(mode)))
+
+
+def roast_embed_bwd(desc: RoastEmbedDesc, rows, table_ids, dOut, dM, mode: int = ROAST_REDUCE_ATOMIC, ws=None,
+                    stream=None):
+    torch = _torch()
+    N = rows.numel()
+    if tuple(dOut.shape) != (N, desc.D) or dM.numel() != desc.m_size:
+        raise ValueError("dOut must be N x D and dM must have m_size entries")
+    wp, wb = (0, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+    _check(load().roast_embed_bwd(C.byref(desc), N, _vec(rows, torch.int64, "rows"),
+                                  _vec(table_ids, torch.int32, "table_ids"), _vec(dOut, torch.float32, "dOut"),
+                                  _vec(dM, torch.float32, "dM"), int(mode), wp, wb, _stream(stream)),
+           "roast_embed_bwd")
+    return dM

@@ -1,0 +1,195 @@
+// C-ABI entry points: argument validation on the host, then dispatch to the kernels.
+// Nothing here allocates device memory or synchronises.
+#include "roast.h"
+#include "roast_internal.hpp"
+
+using namespace roast;
+
+namespace {
+
+roast_status check_hash(const roast_hash& h) {
+  if (h.P < 2 || h.P >= (1ull << 32) || h.align < 1) return ROAST_ERR_RANGE;
+  const uint64_t c[8] = {h.a0, h.a1, h.a2, h.a3, h.s0, h.s1, h.s2, h.s3};
+  for (uint64_t v : c)
+    if (v >= h.P) return ROAST_ERR_RANGE;
+  return ROAST_OK;
+}
+
+roast_status make_mm_args(const roast_mm_desc* d, int64_t I, MMArgs* a) {
+  if (!d || I < 0) return ROAST_ERR_ARG;
+  if (d->H <= 0 || d->O <= 0 || d->Z1 <= 0 || d->Z2 <= 0) return ROAST_ERR_SHAPE;
+  if (d->H >= (1ll << 31) || d->O >= (1ll << 31) || I >= (1ll << 31)) return ROAST_ERR_UNSUPPORTED;
+  const int64_t L = (int64_t)d->Z1 * d->Z2;
+  if (d->m_size < L) return ROAST_ERR_RANGE;
+  roast_status st = check_hash(d->hash);
+  if (st != ROAST_OK) return st;
+  a->I = I; a->H = d->H; a->O = d->O; a->Z1 = d->Z1; a->Z2 = d->Z2;
+  a->nTx = (d->H + d->Z1 - 1) / d->Z1;
+  a->nTy = (d->O + d->Z2 - 1) / d->Z2;
+  a->m_size = d->m_size;
+  a->layer = d->layer_id;
+  a->lambda = d->lambda;
+  a->hash = make_hash_dev(d->hash, d->m_size, L);
+  return ROAST_OK;
+}
+
+roast_status make_embed_args(const roast_embed_desc* d, int64_t N, EmbedArgs* a) {
+  if (!d || N < 0) return ROAST_ERR_ARG;
+  if (d->D <= 0 || d->Z <= 0) return ROAST_ERR_SHAPE;
+  if (d->D >= (1ll << 31)) return ROAST_ERR_UNSUPPORTED;
+  if (d->m_size < d->Z) return ROAST_ERR_RANGE;
+  roast_status st = check_hash(d->hash);
+  if (st != ROAST_OK) return st;
+  a->N = N; a->D = d->D; a->Z = d->Z;
+  a->C = (d->D + d->Z - 1) / d->Z;
+  a->m_size = d->m_size;
+  a->lambda = d->lambda;
+  a->hash = make_hash_dev(d->hash, d->m_size, d->Z);
+  return ROAST_OK;
+}
+
+bool dtype_ok(roast_dtype dt) { return dt == ROAST_F32 || dt == ROAST_BF16; }
+bool mode_ok(roast_reduce_mode m) { return m == ROAST_REDUCE_ATOMIC || m == ROAST_REDUCE_DETERMINISTIC; }
+
+}  // namespace
+
+extern "C" {
+
+const char* roast_status_string(roast_status s) {
+  switch (s) {
+    case ROAST_OK: return "ok";
+    case ROAST_ERR_ARG: return "bad argument (null pointer, negative size, leading dimension too small or bad enum)";
+    case ROAST_ERR_SHAPE: return "bad shape (H, O, Z1, Z2, D and Z must be positive)";
+    case ROAST_ERR_RANGE: return "block does not fit in M or hash parameters out of range";
+    case ROAST_ERR_WORKSPACE: return "workspace missing or too small";
+    case ROAST_ERR_HIP: return "HIP runtime error";
+    case ROAST_ERR_UNSUPPORTED: return "unsupported combination";
+  }
+  return "unknown status";
+}
+
+roast_status roast_tile_index(const roast_mm_desc* d, int64_t* off_host, int8_t* sgn_host) {
+  MMArgs a;
+  roast_status st = make_mm_args(d, 0, &a);
+  if (st != ROAST_OK) return st;
+  for (int64_t x = 0; x < a.nTx; ++x)
+    for (int64_t y = 0; y < a.nTy; ++y) {
+      if (off_host) off_host[x * a.nTy + y] = block_offset(a.hash, a.layer, (uint64_t)x, (uint64_t)y);
+      if (sgn_host) sgn_host[x * a.nTy + y] = (int8_t)block_sign(a.hash, a.layer, (uint64_t)x, (uint64_t)y);
+    }
+  return ROAST_OK;
+}
+
+roast_status roast_tile_index_device(const roast_mm_desc* d, int64_t* off_dev, int8_t* sgn_dev, void* stream) {
+  MMArgs a;
+  roast_status st = make_mm_args(d, 0, &a);
+  if (st != ROAST_OK) return st;
+  if (!off_dev || !sgn_dev) return ROAST_ERR_ARG;
+  return tile_index_launch(a, off_dev, sgn_dev, (hipStream_t)stream);
+}
+
+roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                                      const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream) {
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (N == 0) return ROAST_OK;
+  if (!rows || !table_ids || !off_dev || !sgn_dev) return ROAST_ERR_ARG;
+  return chunk_index_launch(a, rows, table_ids, off_dev, sgn_dev, (hipStream_t)stream);
+}
+
+roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                          const float* M, void* Y, int64_t ldy, void* stream) {
+  MMArgs a;
+  roast_status st = make_mm_args(d, I, &a);
+  if (st != ROAST_OK) return st;
+  if (!dtype_ok(dt)) return ROAST_ERR_ARG;
+  if (I == 0) return ROAST_OK;
+  if (!X || !M || !Y || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
+  if (dt == ROAST_BF16) {
+    st = mfma_mm_fwd(a, X, ldx, M, Y, ldy, (hipStream_t)stream);
+    if (st != ROAST_ERR_UNSUPPORTED) return st;
+  }
+  return generic_mm_fwd(a, dt, X, ldx, M, Y, ldy, (hipStream_t)stream);
+}
+
+roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
+                             const float* M, void* dX, int64_t ldx, void* stream) {
+  MMArgs a;
+  roast_status st = make_mm_args(d, I, &a);
+  if (st != ROAST_OK) return st;
+  if (!dtype_ok(dt)) return ROAST_ERR_ARG;
+  if (I == 0) return ROAST_OK;
+  if (!dY || !M || !dX || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
+  if (dt == ROAST_BF16) {
+    st = mfma_mm_bwd_dx(a, dY, ldy, M, dX, ldx, (hipStream_t)stream);
+    if (st != ROAST_ERR_UNSUPPORTED) return st;
+  }
+  return generic_mm_bwd_dx(a, dt, dY, ldy, M, dX, ldx, (hipStream_t)stream);
+}
+
+size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode) {
+  MMArgs a;
+  if (make_mm_args(d, I, &a) != ROAST_OK) return 0;
+  if (mode != ROAST_REDUCE_DETERMINISTIC || I == 0) return 0;
+  return dm_det_workspace_bytes(a);
+}
+
+roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                             const void* dY, int64_t ldy, float* dM, roast_reduce_mode mode, void* ws,
+                             size_t ws_bytes, void* stream) {
+  MMArgs a;
+  roast_status st = make_mm_args(d, I, &a);
+  if (st != ROAST_OK) return st;
+  if (!dtype_ok(dt) || !mode_ok(mode)) return ROAST_ERR_ARG;
+  if (I == 0) return ROAST_OK;
+  if (!X || !dY || !dM || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
+  if (mode == ROAST_REDUCE_DETERMINISTIC) {
+    const size_t need = dm_det_workspace_bytes(a);
+    if (need == 0) return ROAST_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < need) return ROAST_ERR_WORKSPACE;
+    return dm_det_run(a, dt, X, ldx, dY, ldy, dM, ws, (hipStream_t)stream);
+  }
+  if (dt == ROAST_BF16) {
+    st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, dM, nullptr, 0, (hipStream_t)stream);
+    if (st != ROAST_ERR_UNSUPPORTED) return st;
+  }
+  return generic_mm_bwd_dM_atomic(a, dt, X, ldx, dY, ldy, dM, (hipStream_t)stream);
+}
+
+roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t* rows, const uint32_t* table_ids,
+                             const float* M, float* out, void* stream) {
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (N == 0) return ROAST_OK;
+  if (!rows || !table_ids || !M || !out) return ROAST_ERR_ARG;
+  return embed_fwd_launch(a, rows, table_ids, M, out, (hipStream_t)stream);
+}
+
+size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_reduce_mode mode) {
+  EmbedArgs a;
+  if (make_embed_args(d, N, &a) != ROAST_OK) return 0;
+  if (mode != ROAST_REDUCE_DETERMINISTIC || N == 0) return 0;
+  return embed_det_workspace_bytes(a);
+}
+
+roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t* rows, const uint32_t* table_ids,
+                             const float* dOut, float* dM, roast_reduce_mode mode, void* ws, size_t ws_bytes,
+                             void* stream) {
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (!mode_ok(mode)) return ROAST_ERR_ARG;
+  if (N == 0) return ROAST_OK;
+  if (!rows || !table_ids || !dOut || !dM) return ROAST_ERR_ARG;
+  if (mode == ROAST_REDUCE_DETERMINISTIC) {
+    const size_t need = embed_det_workspace_bytes(a);
+    if (need == 0) return ROAST_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < need) return ROAST_ERR_WORKSPACE;
+    return embed_bwd_det_run(a, rows, table_ids, dOut, dM, ws, (hipStream_t)stream);
+  }
+  return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, (hipStream_t)stream);
+}
+
+}  // extern "C"

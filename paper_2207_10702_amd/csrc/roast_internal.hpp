@@ -1,0 +1,90 @@
+// Internal declarations shared by the library's translation units (not part of the C-ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "roast.h"
+#include "roast_hash.hpp"
+
+namespace roast {
+
+// One validated ROAST-MM call.
+struct MMArgs {
+  int64_t I, H, O;
+  int32_t Z1, Z2;
+  int64_t nTx, nTy;  // tile grid
+  int64_t m_size;
+  uint32_t layer;
+  float lambda;
+  HashDev hash;
+};
+
+// One validated lookup call.
+struct EmbedArgs {
+  int64_t N, D;
+  int32_t Z;
+  int64_t C;  // chunks per row = ceil(D/Z)
+  int64_t m_size;
+  float lambda;
+  HashDev hash;
+};
+
+inline roast_status hip_status(hipError_t e) { return e == hipSuccess ? ROAST_OK : ROAST_ERR_HIP; }
+
+// bfloat16 <-> float on raw bit patterns (round to nearest even; NaN stays NaN).
+__host__ __device__ inline float bf16_bits_to_float(uint16_t b) {
+  union { uint32_t u; float f; } v;
+  v.u = (uint32_t)b << 16;
+  return v.f;
+}
+__host__ __device__ inline uint16_t float_to_bf16_bits(float f) {
+  union { uint32_t u; float f; } v;
+  v.f = f;
+  if ((v.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((v.u >> 16) | 0x40u);
+  v.u += 0x7fffu + ((v.u >> 16) & 1u);
+  return (uint16_t)(v.u >> 16);
+}
+
+// ---- generic kernels: any shape, any tile size, fp32 or bf16 activations (roast_mm_generic.hip)
+roast_status generic_mm_fwd(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx, const float* M,
+                            void* Y, int64_t ldy, hipStream_t s);
+roast_status generic_mm_bwd_dx(const MMArgs& a, roast_dtype dt, const void* dY, int64_t ldy, const float* M,
+                               void* dX, int64_t ldx, hipStream_t s);
+roast_status generic_mm_bwd_dM_atomic(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx,
+                                      const void* dY, int64_t ldy, float* dM, hipStream_t s);
+
+// Generic dM product with an explicit number of I-splits; Gws as for mfma_mm_bwd_dM below.
+roast_status generic_dm_launch(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx, const void* dY,
+                               int64_t ldy, float* dM, float* Gws, int splits, hipStream_t s);
+
+// ---- deterministic dM reduction (roast_reduce.hip)
+// Workspace layout: [G: S*H*O floats][tile keys: nT uint64][sorted tile ids: nT uint32]
+int dm_det_splits(const MMArgs& a);                       // S: how many partial products of G are kept
+size_t dm_det_workspace_bytes(const MMArgs& a);
+roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx, const void* dY,
+                        int64_t ldy, float* dM, void* ws, hipStream_t s);
+
+// ---- bf16 MFMA kernels (roast_mm_mfma.hip): return ROAST_ERR_UNSUPPORTED when the shape does not
+// meet their divisibility rules; the caller then falls back to the generic kernels.
+roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy,
+                         hipStream_t s);
+roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx,
+                            hipStream_t s);
+// Gws == nullptr: atomically add lambda*sign*G into dM.  Gws != nullptr: store raw per-split G there
+// ([splits][H][O] floats) for the deterministic reduction; `splits` must equal dm_det_splits().
+roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
+                            float* Gws, int splits, hipStream_t s);
+
+// ---- lookup kernels (roast_embed.hip)
+roast_status embed_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
+                              float* out, hipStream_t s);
+roast_status embed_bwd_atomic_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables,
+                                     const float* dOut, float* dM, hipStream_t s);
+size_t embed_det_workspace_bytes(const EmbedArgs& a);
+roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
+                               float* dM, void* ws, hipStream_t s);
+roast_status chunk_index_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, int64_t* off,
+                                int8_t* sgn, hipStream_t s);
+roast_status tile_index_launch(const MMArgs& a, int64_t* off, int8_t* sgn, hipStream_t s);
+
+}  // namespace roast

@@ -1,0 +1,137 @@
+// Deterministic reduction of the ROAST-MM gradient into M (gradient equation of Section 3.3 of
+// arXiv 2207.10702: every slot of M receives the lambda-scaled sum of the gradients of all
+// virtual weights hashed to it).
+//
+// Steps: (1) the tile table (offset, sign) is computed on the device and the tiles are ranked by
+// (offset, tile id); (2) the per-tile products G = X^T dY are written, unscaled, to the workspace,
+// one copy per I-split; (3) one thread per slot j of M walks the tiles whose interval
+// [offset, offset + Z1*Z2) covers j -- a contiguous run of the ranked table because all tiles have
+// the same length -- and adds their contributions in rank order, splits in index order.  No
+// atomics, so the result is bit-identical from run to run.
+#include "roast_internal.hpp"
+
+namespace roast {
+namespace {
+
+constexpr int64_t kMaxTilesDet = 1 << 17;  // the ranking pass is quadratic in the number of tiles
+
+struct DetLayout {
+  size_t g_off, key_off, soff_off, order_off, sgn_off, total;
+};
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline DetLayout det_layout(const MMArgs& a, int splits) {
+  const size_t nT = (size_t)(a.nTx * a.nTy);
+  DetLayout l;
+  l.g_off = 0;
+  l.key_off = align_up((size_t)splits * (size_t)a.H * (size_t)a.O * sizeof(float), 256);
+  l.soff_off = l.key_off + align_up(nT * sizeof(int64_t), 256);
+  l.order_off = l.soff_off + align_up(nT * sizeof(int64_t), 256);
+  l.sgn_off = l.order_off + align_up(nT * sizeof(uint32_t), 256);
+  l.total = l.sgn_off + align_up(nT * sizeof(int8_t), 256);
+  return l;
+}
+
+// rank of tile t among all tiles by (offset, id); writes the sorted offsets and the permutation.
+__global__ __launch_bounds__(256) void k_rank_tiles(int64_t nT, const int64_t* __restrict__ off,
+                                                    int64_t* __restrict__ sorted_off, uint32_t* __restrict__ order) {
+  __shared__ int64_t buf[256];
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t mine = t < nT ? off[t] : 0;
+  int64_t rank = 0;
+  for (int64_t base = 0; base < nT; base += 256) {
+    const int64_t u = base + threadIdx.x;
+    buf[threadIdx.x] = u < nT ? off[u] : INT64_MAX;
+    __syncthreads();
+    const int lim = (int)min((int64_t)256, nT - base);
+    for (int q = 0; q < lim; ++q) {
+      const int64_t o = buf[q];
+      rank += (o < mine || (o == mine && base + q < t)) ? 1 : 0;
+    }
+    __syncthreads();
+  }
+  if (t < nT) {
+    sorted_off[rank] = mine;
+    order[rank] = (uint32_t)t;
+  }
+}
+
+__global__ __launch_bounds__(256) void k_dm_gather(MMArgs a, int splits, const float* __restrict__ G,
+                                                   const int64_t* __restrict__ sorted_off,
+                                                   const uint32_t* __restrict__ order, const int8_t* __restrict__ sgn,
+                                                   float* __restrict__ dM) {
+  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (j >= a.m_size) return;
+  const int64_t nT = a.nTx * a.nTy, L = (int64_t)a.Z1 * a.Z2;
+  // first ranked tile with offset > j - L
+  int64_t lo = 0, hi = nT;
+  while (lo < hi) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (sorted_off[mid] > j - L) hi = mid; else lo = mid + 1;
+  }
+  float total = 0.f;
+  bool any = false;
+  for (int64_t q = lo; q < nT; ++q) {
+    const int64_t o = sorted_off[q];
+    if (o > j) break;
+    const uint32_t t = order[q];
+    const int64_t p = j - o;
+    const int64_t h = (int64_t)(t / a.nTy) * a.Z1 + p / a.Z2;
+    const int64_t c = (int64_t)(t % a.nTy) * a.Z2 + p % a.Z2;
+    if (h >= a.H || c >= a.O) continue;
+    float acc = 0.f;
+    for (int s = 0; s < splits; ++s) acc += G[((int64_t)s * a.H + h) * a.O + c];
+    total += a.lambda * (float)sgn[t] * acc;
+    any = true;
+  }
+  if (any) dM[j] += total;
+}
+
+}  // namespace
+
+int dm_det_splits(const MMArgs& a) {
+  // A fixed function of the shape only, so that the summation order never depends on the machine.
+  const int64_t tiles = ((a.O + 255) / 256) * ((a.H + 255) / 256);
+  int64_t s = (512 + tiles - 1) / tiles;
+  const int64_t max_s = (a.I + 511) / 512;
+  if (s > max_s) s = max_s;
+  if (s > 64) s = 64;
+  if (s < 1) s = 1;
+  return (int)s;
+}
+
+size_t dm_det_workspace_bytes(const MMArgs& a) {
+  if (a.nTx * a.nTy > kMaxTilesDet) return 0;
+  return det_layout(a, dm_det_splits(a)).total;
+}
+
+roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx, const void* dY, int64_t ldy,
+                        float* dM, void* ws, hipStream_t s) {
+  const int splits = dm_det_splits(a);
+  const DetLayout l = det_layout(a, splits);
+  char* base = (char*)ws;
+  float* G = (float*)(base + l.g_off);
+  int64_t* keys = (int64_t*)(base + l.key_off);
+  int64_t* soff = (int64_t*)(base + l.soff_off);
+  uint32_t* order = (uint32_t*)(base + l.order_off);
+  int8_t* sgn = (int8_t*)(base + l.sgn_off);
+  const int64_t nT = a.nTx * a.nTy;
+
+  roast_status st = tile_index_launch(a, keys, sgn, s);
+  if (st != ROAST_OK) return st;
+  hipLaunchKernelGGL(k_rank_tiles, dim3((unsigned)((nT + 255) / 256)), dim3(256), 0, s, nT, keys, soff, order);
+  st = hip_status(hipGetLastError());
+  if (st != ROAST_OK) return st;
+
+  st = ROAST_ERR_UNSUPPORTED;
+  if (dt == ROAST_BF16) st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, nullptr, G, splits, s);
+  if (st == ROAST_ERR_UNSUPPORTED) st = generic_dm_launch(a, dt, X, ldx, dY, ldy, nullptr, G, splits, s);
+  if (st != ROAST_OK) return st;
+
+  hipLaunchKernelGGL(k_dm_gather, dim3((unsigned)((a.m_size + 255) / 256)), dim3(256), 0, s, a, splits, G, soff,
+                     order, sgn, dM);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace roast

@@ -1,0 +1,83 @@
+"""CPU-side checks of the HIP library: it loads, exports everything include/roast.h declares,
+validates arguments, and its host evaluation of the tile map agrees bit for bit with the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2207_10702_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "roast.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(roast_[A-Za-z0-9_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.load()
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+@pytest.mark.parametrize("name", [n for n, c in wl.CONFIGS.items() if isinstance(c, wl.MMConfig)])
+def test_host_tile_index_is_bit_exact_on_every_config_grid(name):
+    cfg = wl.CONFIGS[name]
+    h = wl.draw_hash(np.random.default_rng(cfg.seed + 1))
+    for layer in cfg.layers:
+        d = binding.mm_desc(layer.H, layer.O, cfg.Z1, cfg.Z2, cfg.m_size, layer.layer_id, cfg.lam, h)
+        off, sgn = binding.roast_tile_index(d)
+        eoff, esgn = oracle.tile_index(h, layer.layer_id, layer.H, layer.O, cfg.Z1, cfg.Z2, cfg.m_size)
+        assert np.array_equal(off, eoff) and np.array_equal(sgn, esgn)
+
+
+def test_host_tile_index_random_parameters_primes_alignment_and_edges():
+    rng = np.random.default_rng(77)
+    primes = [2, 3, 65537, 2147483647, 4294967291]
+    for trial in range(300):
+        P = primes[trial % len(primes)]
+        h = dict(P=P, use_sign=int(rng.integers(0, 2)), align=int(rng.integers(1, 6)))
+        for k in ("a0", "a1", "a2", "a3", "s0", "s1", "s2", "s3"):
+            h[k] = int(rng.integers(0, P))
+        Z1, Z2 = int(rng.integers(1, 9)), int(rng.integers(1, 9))
+        H, O = int(rng.integers(1, 60)), int(rng.integers(1, 60))
+        m = Z1 * Z2 + int(rng.integers(0, 3000)) * int(rng.integers(0, 2))
+        layer = int(rng.integers(0, 1 << 32))
+        d = binding.mm_desc(H, O, Z1, Z2, m, layer, 1.0, h)
+        off, sgn = binding.roast_tile_index(d)
+        eoff, esgn = oracle.tile_index(h, layer, H, O, Z1, Z2, m)
+        assert np.array_equal(off, eoff) and np.array_equal(sgn, esgn)
+
+
+def test_argument_validation_returns_status_codes_without_touching_the_gpu():
+    lib = binding.load()
+    h = wl.draw_hash(np.random.default_rng(0))
+    ok = binding.mm_desc(64, 64, 8, 8, 1000, 0, 1.0, h)
+    assert lib.roast_tile_index(C.byref(ok), None, None) == 0
+    assert lib.roast_tile_index(None, None, None) == 1
+    bad_shape = binding.mm_desc(64, 0, 8, 8, 1000, 0, 1.0, h)
+    assert lib.roast_tile_index(C.byref(bad_shape), None, None) == 2
+    too_small = binding.mm_desc(64, 64, 8, 8, 63, 0, 1.0, h)
+    assert lib.roast_tile_index(C.byref(too_small), None, None) == 3
+    bad_hash = binding.mm_desc(64, 64, 8, 8, 1000, 0, 1.0, dict(h, a1=h["P"]))
+    assert lib.roast_tile_index(C.byref(bad_hash), None, None) == 3
+    # null tensors are refused before any launch
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, None, 64, None, None, 64, None) == 1
+    assert lib.roast_mm_fwd(C.byref(ok), 7, 4, 1, 64, 1, 1, 64, None) == 1          # bad dtype enum
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, 1, 63, 1, 1, 64, None) == 1          # ldx < H
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 0, None, 64, None, None, 64, None) == 0  # I == 0: no-op
+    assert lib.roast_mm_bwd_dM(C.byref(ok), 0, 4, 1, 64, 1, 64, 1, 1, None, 0, None) == 4  # no workspace
+    e = binding.embed_desc(16, 4, 3, 1.0, h)
+    assert lib.roast_embed_fwd(C.byref(e), 5, 1, 1, 1, 1, None) == 3
+    with pytest.raises(binding.RoastError) as ei:
+        binding.roast_tile_index(too_small)
+    assert ei.value.status == 3 and "fit" in str(ei.value)
+    assert lib.roast_mm_bwd_dM_workspace(C.byref(ok), 128, 0) == 0
+    assert lib.roast_mm_bwd_dM_workspace(C.byref(ok), 128, 1) > 64 * 64 * 4
