@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the ROAST hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic input:
+  * ROAST-MM on the BERT-base-FFN configuration (bf16 activations, fp32 accumulation, two chained
+    layers 768->3072->768 sharing one M at 100x compression, 8192 tokens): forward of both layers,
+    then dX and dM of both layers (6 calls);
+  * the ROAST lookup on the DLRM-shaped configuration (26 tables, 10M rows x 128, chunks of 32 hashed
+    into 1.28M slots, 65536 x 26 Zipf(1.05) lookups): forward and gradient scatter-add (2 calls).
+All inputs are resident in HBM before the timed region.  `value` is the ROAST-MM fwd+bwd rate in
+TFLOP/s (3 x 2*I*H*O per layer over the time of the six MM calls); the lookup's GB/s is reported
+next to it under "embedding".  Per-call times are measured with HIP events on the launch stream.
+
+Prints ONE JSON line.  The CPU oracle is timed beside it on a bounded sample (cpu_baseline).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 bf16 FLOP/clk/CU x 2.4 GHz, dense
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
+    p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
+    p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the hot path has no multi-GPU leg.",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2207_10702_amd import binding as roast, workloads as wl
+    from tests.util import to_dev
+
+    roast.load()
+    torch.cuda.set_device(0)
+    mode = roast.ROAST_REDUCE_ATOMIC if args.reduce == "atomic" else roast.ROAST_REDUCE_DETERMINISTIC
+
+    # ------------------------------------------------------------------ inputs (resident before timing)
+    mcfg = wl.CONFIGS["cfg2_bert_ffn_bf16"]
+    mi = wl.make_mm_inputs(mcfg)
+    l1, l2 = mcfg.layers
+    d1 = roast.mm_desc(l1.H, l1.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l1.layer_id, mcfg.lam, mi.hash)
+    d2 = roast.mm_desc(l2.H, l2.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l2.layer_id, mcfg.lam, mi.hash)
+    M = to_dev(mi.M)
+    X = to_dev(mi.X[l1.name])
+    dY = to_dev(mi.dY[l2.name])
+    I = mcfg.I
+    H1 = torch.empty((I, l1.O), dtype=torch.bfloat16, device="cuda")
+    Y = torch.empty((I, l2.O), dtype=torch.bfloat16, device="cuda")
+    dH1 = torch.empty((I, l1.O), dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty((I, l1.H), dtype=torch.bfloat16, device="cuda")
+    dM = torch.zeros(mcfg.m_size, dtype=torch.float32, device="cuda")
+    ws_bytes = max(roast.roast_mm_bwd_dM_workspace(d1, I, mode), roast.roast_mm_bwd_dM_workspace(d2, I, mode), 1)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+
+    ecfg = wl.CONFIGS["cfg4_dlrm_embed_f32"]
+    ei = wl.make_embed_inputs(ecfg)
+    ed = roast.embed_desc(ecfg.D, ecfg.Z, ecfg.m_size, ecfg.lam, ei.hash)
+    eM = to_dev(ei.M)
+    rows, tables, dOut = to_dev(ei.rows), to_dev(ei.tables), to_dev(ei.dOut)
+    N = ecfg.N
+    out = torch.empty((N, ecfg.D), dtype=torch.float32, device="cuda")
+    edM = torch.zeros(ecfg.m_size, dtype=torch.float32, device="cuda")
+
+    names = []
+    if not args.embed_only:
+        names += ["mm_fwd_l1", "mm_fwd_l2", "mm_bwd_dx_l2", "mm_bwd_dM_l2", "mm_bwd_dx_l1", "mm_bwd_dM_l1"]
+    if not args.mm_only:
+        names += ["embed_fwd", "embed_bwd"]
+
+    def step(ev=None):
+        k = 0
+
+        def mark():
+            nonlocal k
+            if ev is not None:
+                ev[k].record()
+            k += 1
+
+        mark()
+        if not args.embed_only:
+            roast.roast_mm_fwd(d1, X, M, H1); mark()
+            roast.roast_mm_fwd(d2, H1, M, Y); mark()
+            roast.roast_mm_bwd_dx(d2, dY, M, dH1); mark()
+            roast.roast_mm_bwd_dM(d2, H1, dY, dM, mode, ws); mark()
+            roast.roast_mm_bwd_dx(d1, dH1, M, dX); mark()
+            roast.roast_mm_bwd_dM(d1, X, dH1, dM, mode, ws); mark()
+        if not args.mm_only:
+            roast.roast_embed_fwd(ed, rows, tables, eM, out); mark()
+            roast.roast_embed_bwd(ed, rows, tables, dOut, edM); mark()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(len(names) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(evs[s])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    per_call = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
+                for i, n in enumerate(names)}                       # ms, mean over the timed steps
+
+    result = {"metric": "ROAST-MM fwd+bwd TFLOP/s (% MFMA peak); ROAST-embedding GB/s (% HBM peak)",
+              "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+              "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+              "dtype": "bf16", "data": "synthetic",
+              "config": {"workload": "cfg2_bert_ffn_bf16 (ROAST-MM 8192x768x3072 + 8192x3072x768, 64x64 tiles, "
+                                     "|M|=47185) + cfg4_dlrm_embed_f32 (1703936 lookups x 128, chunk 32, |M|=1.28M)",
+                         "reduce": args.reduce},
+              "per_call_ms": per_call}
+
+    flop_layer = {"l1": 2.0 * I * l1.H * l1.O, "l2": 2.0 * I * l2.H * l2.O}
+    if not args.embed_only:
+        mm_ms = sum(v for k, v in per_call.items() if k.startswith("mm_"))
+        mm_flop = 3.0 * (flop_layer["l1"] + flop_layer["l2"])
+        tflops = mm_flop / (mm_ms * 1e-3) / 1e12
+        result["value"] = tflops
+        result["mm_ms"] = mm_ms
+        result["pct_mfma_peak"] = 100.0 * tflops / PEAK_BF16_TFLOPS
+        dom = max((k for k in per_call if k.startswith("mm_")), key=lambda k: per_call[k])
+        ach = flop_layer[dom[-2:]] / (per_call[dom] * 1e-3) / 1e12
+        result["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                              "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+    if not args.mm_only:
+        # compulsory HBM bytes: output (or dOut) once, ids once, M (and dM read+write) once
+        ids = N * (8 + 4)
+        bytes_fwd = N * ecfg.D * 4 + ids + ecfg.m_size * 4
+        bytes_bwd = N * ecfg.D * 4 + ids + 2 * ecfg.m_size * 4
+        gbs_f = bytes_fwd / (per_call["embed_fwd"] * 1e-3) / 1e9
+        gbs_b = bytes_bwd / (per_call["embed_bwd"] * 1e-3) / 1e9
+        tot = (bytes_fwd + bytes_bwd) / ((per_call["embed_fwd"] + per_call["embed_bwd"]) * 1e-3) / 1e9
+        result["embedding"] = {"value": tot, "unit": "GB/s", "pct_hbm_peak": 100.0 * tot / PEAK_HBM_GBS,
+                               "fwd_GBs": gbs_f, "bwd_GBs": gbs_b, "bytes_fwd": bytes_fwd, "bytes_bwd": bytes_bwd,
+                               "roofline": {"kernel": "embed_fwd", "bound": "hbm", "achieved": gbs_f,
+                                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
+                                            "traffic": None}}
+        if args.embed_only:
+            result["value"] = tot
+            result["unit"] = "GB/s"
+            result["dtype"] = "f32"
+            result["roofline"] = result["embedding"]["roofline"]
+
+    if not args.no_cpu_baseline and not args.embed_only:
+        import oracle
+        # bounded sample: the first `rows_s` tokens through forward, dX and dW (+ scatter) of both layers
+        rows_s = 1024
+        Xs = wl.act_as_f64(mi.X[l1.name][:rows_s])
+        dYs = wl.act_as_f64(mi.dY[l2.name][:rows_s])
+        lam = float(np.float32(mcfg.lam))
+        c0 = time.perf_counter()
+        W1 = oracle.materialize_w(mi.hash, l1.layer_id, l1.H, l1.O, mcfg.Z1, mcfg.Z2, lam, mi.M)
+        W2 = oracle.materialize_w(mi.hash, l2.layer_id, l2.H, l2.O, mcfg.Z1, mcfg.Z2, lam, mi.M)
+        h1 = oracle.mm_fwd(Xs, W1)
+        oracle.mm_fwd(h1, W2)
+        dh1 = oracle.mm_bwd_dx(dYs, W2)
+        g = oracle.mm_bwd_dm(mi.hash, l2.layer_id, mcfg.Z1, mcfg.Z2, mcfg.m_size, lam, h1, dYs)
+        oracle.mm_bwd_dx(dh1, W1)
+        oracle.mm_bwd_dm(mi.hash, l1.layer_id, mcfg.Z1, mcfg.Z2, mcfg.m_size, lam, Xs, dh1, dM=g)
+        c1 = time.perf_counter()
+        flop_s = 3.0 * (flop_layer["l1"] + flop_layer["l2"]) * rows_s / I
+        result["cpu_baseline"] = {"value": flop_s / (c1 - c0) / 1e12, "unit": "TFLOP/s",
+                                  "cores": oracle.num_threads(), "kind": "oracle",
+                                  "sample": f"first {rows_s} of {I} tokens of cfg2 through fwd, dX and dM of both "
+                                            f"layers (W materialised element by element, fp64 triple loops), "
+                                            f"{c1 - c0:.1f} s"}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -126,7 +126,18 @@ def test_mm_fp32_matches_oracle(roast, shape):
     assert rel_err(got["dM_det"], ref["dM"]) <= F32_TOL
 
 
-@pytest.mark.parametrize("shape", MM_SHAPES)
+# shapes that meet the MFMA kernels' divisibility rules (several 256x256 workgroup tiles, ragged I and
+# ragged O / H against the workgroup tile, 64- and 128-wide hash tiles, |M| == tile)
+MFMA_SHAPES = [
+    (300, 128, 320, 64, 64, 20000),
+    (513, 256, 128, 128, 128, 40000),
+    (256, 192, 96, 64, 32, 9000),
+    (1000, 64, 576, 64, 64, 4096),
+    (700, 640, 64, 64, 64, 5000),
+]
+
+
+@pytest.mark.parametrize("shape", MM_SHAPES + MFMA_SHAPES)
 def test_mm_bf16_matches_oracle(roast, shape):
     got, ref = run_mm(roast, "bf16", 200 + shape[0], *shape, lam=1.5)
     for k in ("Y", "dX", "dM"):
