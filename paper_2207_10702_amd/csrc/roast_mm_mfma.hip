@@ -2,28 +2,31 @@
 // arXiv 2207.10702): forward Y = X*W, dX = dY*W^T and the per-tile products of dM = scatter(X^T*dY),
 // with W recovered from M tile by tile and never written to memory.
 //
-// One workgroup = 256 threads = 4 waves (2 x 2) computes a BM x BN block of the output with
-// v_mfma_f32_32x32x16_bf16; each wave owns a (BM/2) x (BN/2) sub-block held in fp32 accumulators.
-// The contraction runs in steps of BK = 64 through two LDS stages (global -> registers -> LDS while
-// the MFMAs of the previous step run).  Operands sit in LDS in one of two layouts:
-//   KMAJ: [row][k], 128-byte rows, 16-byte chunks XOR-swizzled by (row & 7); a lane fetches its
-//         8 contraction values with one ds_read_b128.  Used when memory is contraction-contiguous
-//         (X in forward, dY in dX, and the M tile in dX where the tile's rows run along O).
-//   MMAJ: [k][col], rows padded by 64 bytes; a lane fetches its values with two transposing reads
-//         (ds_read_b64_tr_b16).  Used when memory is contiguous along the output dimension
-//         (the M tile in forward; X and dY in dM, whose contraction runs over the token rows).
-// The weight operand is produced on the fly: fp32 values of M at the tile's hashed offset are
-// multiplied by the tile's sign, rounded to bf16 and written to LDS.  The tile table (offset, sign)
-// of the tiles a workgroup touches is computed by its own threads into LDS at kernel start.
-// lambda is applied to the fp32 accumulators in the epilogue.
+// One workgroup = 256 threads = 4 waves (WGM x WGN) computes a BM x BN block of the output with
+// v_mfma_f32_32x32x16_bf16; each wave owns a (BM/WGM) x (BN/WGN) sub-block in fp32 accumulators.
+// The contraction runs in steps of BK = 64: the next step's operands are fetched from global
+// memory into registers while the MFMAs of the current step read LDS, then written to LDS between
+// two barriers.  Two workgroups share a CU, so one computes while the other moves data.
+//
+// Both operands sit in LDS as [row][k] with 128-byte rows whose 16-byte chunks are XOR-swizzled,
+// so a lane fetches the 8 contraction values of its row with one conflict-free ds_read_b128
+// (transposing LDS reads were measured at a quarter of that bandwidth).  Whatever is not
+// contraction-contiguous in memory is transposed in registers on its way to LDS:
+//   forward: X rows are copied as they are; the hashed weight tile (fp32, contiguous along O) is
+//            loaded as 8(k) x 4(n) register blocks, signed, rounded to bf16 and written per column;
+//   dX:      dY rows are copied; the tile's rows run along O = the contraction, so it is signed,
+//            rounded and copied row by row;
+//   dM:      contraction is over token rows, so X and dY are both transposed as 8 x 8 (8 x 4)
+//            bf16 blocks with v_perm_b32.
+// The tile table (offset, sign) of the tiles a workgroup touches is computed by its own threads
+// into LDS at kernel start.  lambda is applied to the fp32 accumulators in the epilogue, which for
+// forward / dX goes through LDS so that global stores are 16 bytes per lane and row-contiguous.
 #include "roast_internal.hpp"
 
 namespace roast {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
@@ -34,7 +37,7 @@ struct __attribute__((packed, aligned(4))) f4u {  // 4 floats, 4-byte aligned (t
 };
 
 constexpr int BK = 64;
-constexpr int kMaxTable = 1024;  // tile-table entries a workgroup may need
+constexpr int kMaxTable = 512;  // tile-table entries a workgroup may need
 enum { MODE_FWD = 0, MODE_DX = 1, MODE_DM = 2 };
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
@@ -43,33 +46,14 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
-// ---- LDS addressing (byte offsets inside one operand tile)
-__device__ inline int kmaj_off(int row, int chunk) { return row * 128 + ((chunk ^ (row & 7)) << 4); }
-template <int COLS> struct MMaj {
-  static constexpr int kStride = COLS * 2 + 64;           // bytes per k-row
-  static constexpr int kBytes = BK * kStride;
-};
-template <int ROWS> struct KMaj { static constexpr int kBytes = ROWS * 128; };
-
-// Fragment of a 32-row block for one k16 sub-step from a KMAJ tile.
-__device__ inline bf16x8 frag_kmaj(const char* tile, int row0, int ks, int lane) {
-  const int row = row0 + (lane & 31);
-  const int chunk = ks * 2 + (lane >> 5);
-  return *reinterpret_cast<const bf16x8*>(tile + kmaj_off(row, chunk));
+// Byte offset of 16-byte chunk `chunk` (0..7) of row `row` inside an operand tile.
+__device__ inline int lds_off(int row, int chunk) {
+  return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
 }
-// The same fragment from an MMAJ tile via two transposing reads.
-template <int STRIDE>
-__device__ inline bf16x8 frag_mmaj(const char* tile, int col0, int ks, int lane) {
-  const int g = lane >> 4, r = lane & 15, q = r & 3, j = r >> 2;
-  const int krow = ks * 16 + 8 * (g >> 1) + j;
-  const int col = col0 + 16 * (g & 1) + 4 * q;
-  typedef short4v __attribute__((address_space(3))) * lds_p;
-  const char* p = tile + krow * STRIDE + col * 2;
-  short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
-  short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * STRIDE));
-  typedef short short8v __attribute__((ext_vector_type(8)));
-  short8v v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
+
+// Fragment of a 32-row block for k16 sub-step ks: lane -> row (lane & 31), k = 8*(lane >> 5) .. +7.
+__device__ inline bf16x8 frag(const char* tile, int row0, int ks, int lane) {
+  return *reinterpret_cast<const bf16x8*>(tile + lds_off(row0 + (lane & 31), ks * 2 + (lane >> 5)));
 }
 
 struct KernArgs {
@@ -86,28 +70,69 @@ struct KernArgs {
   int rows_per_split;  // DM
 };
 
-template <int MODE, int BM, int BN>
-__global__ __launch_bounds__(256, 1) void k_roast_mfma(KernArgs p) {
-  constexpr bool A_KMAJ = (MODE != MODE_DM);
-  constexpr bool B_KMAJ = (MODE == MODE_DX);
-  constexpr int A_BYTES = A_KMAJ ? KMaj<BM>::kBytes : MMaj<BM>::kBytes;
-  constexpr int B_BYTES = B_KMAJ ? KMaj<BN>::kBytes : MMaj<BN>::kBytes;
-  constexpr int STAGE = A_BYTES + B_BYTES;
-  constexpr int MI = BM / 64, NI = BN / 64;      // 32x32 blocks per wave in each direction
-  constexpr int A_STRIDE = MMaj<BM>::kStride, B_STRIDE = MMaj<BN>::kStride;
+// Transposing loader for a bf16 [BK rows (k)][W cols] tile whose rows are contiguous in memory:
+// each thread owns an 8(k) x CW(cols) block (CW = W/32), loads its 8 row pieces, and writes CW
+// 16-byte chunks (8 k-values of one column) to the [col][k] LDS tile.
+template <int W>
+struct TLoad {
+  static constexpr int CW = W / 32;             // columns per thread: 8 (16-byte loads) or 4 (8-byte loads)
+  static constexpr int DW = CW / 2;             // dwords per row piece
+  static_assert(CW == 8 || CW == 4, "tile width must be 256 or 128");
+  uint32_t r[8][DW];
+  __device__ void load(const uint16_t* src, int64_t ld, int k0, int kmax_row, int col, int kb) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int row = min(k0 + 8 * kb + q, kmax_row);
+      const uint16_t* p = src + (int64_t)row * ld + col;
+      if constexpr (DW == 4) {
+        uint4v v = *reinterpret_cast<const uint4v*>(p);
+        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      } else {
+        uint2v v = *reinterpret_cast<const uint2v*>(p);
+        r[q][0] = v[0]; r[q][1] = v[1];
+      }
+    }
+  }
+  // rows at or beyond k_end are zeroed (they would add into sums that are kept)
+  __device__ void store(char* tile, int k0, int k_end, int colblk, int kb) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q)
+      if (k0 + 8 * kb + q >= k_end) {
+#pragma unroll
+        for (int d = 0; d < DW; ++d) r[q][d] = 0u;
+      }
+#pragma unroll
+    for (int c = 0; c < CW; ++c) {
+      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      uint4v o;
+#pragma unroll
+      for (int pr = 0; pr < 4; ++pr) o[pr] = __builtin_amdgcn_perm(r[2 * pr + 1][c >> 1], r[2 * pr][c >> 1], sel);
+      *reinterpret_cast<uint4v*>(tile + lds_off(colblk * CW + c, kb)) = o;
+    }
+  }
+};
+
+template <int MODE, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
+  static_assert(WGM * WGN == 4, "4 waves");
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+  constexpr int MI = WTM / 32, NI = WTN / 32;    // 32x32 blocks per wave
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+  constexpr int EPI_STRIDE = WTN * 2 + 16;       // bytes per row of a wave's epilogue buffer
 
   extern __shared__ __attribute__((aligned(128))) char smem[];
-  int64_t* s_off = reinterpret_cast<int64_t*>(smem + 2 * STAGE);
-  float* s_sgn = reinterpret_cast<float*>(smem + 2 * STAGE + kMaxTable * 8);
+  char* At = smem;
+  char* Bt = smem + A_BYTES;
+  int64_t* s_off = reinterpret_cast<int64_t*>(smem + A_BYTES + B_BYTES);
+  float* s_sgn = reinterpret_cast<float*>(smem + A_BYTES + B_BYTES + kMaxTable * 8);
 
   const MMArgs& a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
   const int I = (int)a.I;
-  // output block and contraction range
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-  const int Mdim = MODE == MODE_DM ? (int)a.H : I;                      // rows of the output block space
-  const int Ndim = MODE == MODE_FWD ? (int)a.O : (MODE == MODE_DX ? (int)a.H : (int)a.O);
+  const int Mdim = MODE == MODE_DM ? (int)a.H : I;
+  const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
   if (MODE == MODE_DM) {
     k_begin = blockIdx.z * p.rows_per_split;
@@ -120,162 +145,146 @@ __global__ __launch_bounds__(256, 1) void k_roast_mfma(KernArgs p) {
   // DX : entry [kt * TN + xl] for tile (x = n0/Z1 + xl, y = kt), TN = tiles spanned by BN along H
   // DM : entry [xl * TN + yl] for tile (x = m0/Z1 + xl, y = n0/Z2 + yl)
   int TN = 1;
-  if (MODE == MODE_FWD) {
-    const int y0 = n0 / a.Z2;
-    TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
-    const int cnt = (int)a.nTx * TN;
-    for (int e = tid; e < cnt; e += 256) {
-      const uint64_t x = e / TN, y = y0 + e % TN;
-      s_off[e] = block_offset(a.hash, a.layer, x, y);
-      s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
+  {
+    int x0 = 0, y0 = 0, cnt = 0;
+    if (MODE == MODE_FWD) {
+      y0 = n0 / a.Z2;
+      TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
+      cnt = (int)a.nTx * TN;
+    } else if (MODE == MODE_DX) {
+      x0 = n0 / a.Z1;
+      TN = (min(n0 + BN, (int)a.H) - 1) / a.Z1 - x0 + 1;
+      cnt = (int)a.nTy * TN;
+    } else {
+      x0 = m0 / a.Z1; y0 = n0 / a.Z2;
+      TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
+      cnt = ((min(m0 + BM, (int)a.H) - 1) / a.Z1 - x0 + 1) * TN;
     }
-  } else if (MODE == MODE_DX) {
-    const int x0 = n0 / a.Z1;
-    TN = (min(n0 + BN, (int)a.H) - 1) / a.Z1 - x0 + 1;
-    const int cnt = (int)a.nTy * TN;
     for (int e = tid; e < cnt; e += 256) {
-      const uint64_t y = e / TN, x = x0 + e % TN;
-      s_off[e] = block_offset(a.hash, a.layer, x, y);
-      s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
-    }
-  } else {
-    const int x0 = m0 / a.Z1, y0 = n0 / a.Z2;
-    const int TM = (min(m0 + BM, (int)a.H) - 1) / a.Z1 - x0 + 1;
-    TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
-    for (int e = tid; e < TM * TN; e += 256) {
-      const uint64_t x = x0 + e / TN, y = y0 + e % TN;
+      uint64_t x, y;
+      if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
+      else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
+      else { x = x0 + e / TN; y = y0 + e % TN; }
       s_off[e] = block_offset(a.hash, a.layer, x, y);
       s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
     }
   }
   __syncthreads();
 
-  // ---- staging registers
-  constexpr int A_LOADS = BM * BK * 2 / 16 / 256;            // 16-byte loads per thread for the A tile
-  constexpr int BW_LOADS = BK * BN / 4 / 256;                // float4 loads per thread for a weight tile
-  constexpr int BD_LOADS = BK * BN * 2 / 16 / 256;           // 16-byte loads per thread for dY (DM)
-  uint4v a_reg[A_LOADS];
-  floatx4 bw_reg[MODE == MODE_DM ? 1 : BW_LOADS];
-  uint4v bd_reg[MODE == MODE_DM ? BD_LOADS : 1];
-  float bw_sgn[MODE == MODE_DX ? BW_LOADS : 1];
+  // ---- operand staging.  Loads are unconditional: rows / columns outside the problem are
+  // redirected to a valid address and their products are never stored; only the contraction tail
+  // of the dM product is zeroed.
+  // A operand, FWD / DX: BM rows x 8 chunks, thread -> chunk (tid & 7) of rows (tid >> 3) + 32*q
+  constexpr int A_LOADS = BM / 32;
+  uint4v a_reg[MODE == MODE_DM ? 1 : A_LOADS];
+  const uint16_t* a_ptr[MODE == MODE_DM ? 1 : A_LOADS];
+  if (MODE != MODE_DM) {
+#pragma unroll
+    for (int q = 0; q < A_LOADS; ++q)
+      a_ptr[q] = p.A + (int64_t)min(m0 + (tid >> 3) + 32 * q, I - 1) * p.lda + 8 * (tid & 7);
+  }
+  // B operand, FWD: 8(k) x 4(n) fp32 blocks; thread -> column group (tid % (BN/4)), k-blocks kb + KBS*q
+  constexpr int FW_NG = BN / 4, FW_KBS = 256 / FW_NG, FW_BLK = 8 / FW_KBS;
+  floatx4 fw_reg[MODE == MODE_FWD ? FW_BLK * 8 : 1];
+  int fw_yl = 0, fw_nin = 0;
+  float fw_sgn = 1.f;
+  if (MODE == MODE_FWD) {
+    const int n = min(n0 + 4 * (tid % FW_NG), (int)a.O - 4);
+    fw_yl = n / a.Z2 - n0 / a.Z2;
+    fw_nin = n % a.Z2;
+  }
+  // B operand, DX: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (tid & 7) of rows (tid >> 3) + 32*q
+  constexpr int DX_LOADS = BN / 32;
+  floatx4 dx_reg[MODE == MODE_DX ? DX_LOADS * 2 : 1];
+  float dx_sgn[MODE == MODE_DX ? DX_LOADS : 1];
+  int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
+  int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
+  if (MODE == MODE_DX) {
+#pragma unroll
+    for (int q = 0; q < DX_LOADS; ++q) {
+      const int h = min(n0 + (tid >> 3) + 32 * q, (int)a.H - 1);
+      dx_ent[q] = h / a.Z1 - n0 / a.Z1;
+      dx_rowoff[q] = a.Z2 * (h % a.Z1) + 8 * (tid & 7);
+    }
+  }
+  // DM: both operands transposed
+  TLoad<MODE == MODE_DM ? BM : 128> ta;
+  TLoad<MODE == MODE_DM ? BN : 128> tb;
+  const int t_blk = tid & 31, t_kb = tid >> 5;
+  const int ta_col = min(m0 + t_blk * (BM / 32), (int)a.H - BM / 32);
+  const int tb_col = min(n0 + t_blk * (BN / 32), (int)a.O - BN / 32);
 
   auto load_global = [&](int step) {
     const int k0 = k_begin + step * BK;
-    if (A_KMAJ) {
-      // A tile: BM rows x 64 k, 8 chunks of 16 bytes per row
-      const int c = tid & 7, r0 = tid >> 3;
+#ifdef ROAST_EXP_NOLOAD
+    if (step > 0) return;
+#endif
+    if (MODE != MODE_DM) {
 #pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) {
-        const int row = r0 + 32 * q;
-        uint4v v = {0u, 0u, 0u, 0u};
-        if (m0 + row < I) v = *reinterpret_cast<const uint4v*>(p.A + (int64_t)(m0 + row) * p.lda + k0 + 8 * c);
-        a_reg[q] = v;
-      }
-    } else {
-      // DM: A tile = X[i][h0 .. h0+BM): BK rows of BM columns, BM/8 chunks per row
-      constexpr int CPR = BM / 8, RPP = 256 / CPR;
-      const int c = tid % CPR, r0 = tid / CPR;
-#pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) {
-        const int kr = r0 + RPP * q;
-        uint4v v = {0u, 0u, 0u, 0u};
-        if (k0 + kr < k_end && m0 + 8 * c < (int)a.H)
-          v = *reinterpret_cast<const uint4v*>(p.A + (int64_t)(k0 + kr) * p.lda + m0 + 8 * c);
-        a_reg[q] = v;
-      }
+      for (int q = 0; q < A_LOADS; ++q) a_reg[q] = *reinterpret_cast<const uint4v*>(a_ptr[q] + k0);
     }
     if (MODE == MODE_FWD) {
-      // weight tile [k][n]: BN/4 float4 per k-row
-      constexpr int CPR = BN / 4, RPP = 256 / CPR;
-      const int c4 = tid % CPR, r0 = tid / CPR;
-      const int n = n0 + 4 * c4;
-      const int yl = n / a.Z2 - n0 / a.Z2;
-      const int e = (k0 / a.Z1) * TN + yl;
-      const bool ok = n < (int)a.O;
-      const float* base = p.M + (ok ? s_off[e] : 0) + (int64_t)a.Z2 * (k0 % a.Z1) + (n % a.Z2);
-      const float sg = ok ? s_sgn[e] : 0.f;
+      const int e = (k0 / a.Z1) * TN + fw_yl;
+      const float* base = p.M + s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (tid / FW_NG)) + fw_nin;
+      fw_sgn = s_sgn[e];
 #pragma unroll
-      for (int q = 0; q < BW_LOADS; ++q) {
-        const int kr = r0 + RPP * q;
-        floatx4 v = {0.f, 0.f, 0.f, 0.f};
-        if (ok) {
-          const f4u m = *reinterpret_cast<const f4u*>(base + (int64_t)kr * a.Z2);
-          v = floatx4{m.v[0] * sg, m.v[1] * sg, m.v[2] * sg, m.v[3] * sg};
+      for (int b = 0; b < FW_BLK; ++b)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+          const f4u m = *reinterpret_cast<const f4u*>(base + (int64_t)(8 * FW_KBS * b + r) * a.Z2);
+          fw_reg[b * 8 + r] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
         }
-        bw_reg[q] = v;
-      }
     } else if (MODE == MODE_DX) {
-      // weight tile as [n = h][k = o]: 16 float4 per row
-      const int c4 = tid & 15, r0 = tid >> 4;
-      const int kt = k0 / a.Z2;
+      const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
 #pragma unroll
-      for (int q = 0; q < BW_LOADS; ++q) {
-        const int nr = r0 + 16 * q;
-        const int h = n0 + nr;
-        floatx4 v = {0.f, 0.f, 0.f, 0.f};
-        float sg = 0.f;
-        if (h < (int)a.H) {
-          const int xl = h / a.Z1 - n0 / a.Z1;
-          const int e = kt * TN + xl;
-          sg = s_sgn[e];
-          const f4u m = *reinterpret_cast<const f4u*>(p.M + s_off[e] + (int64_t)a.Z2 * (h % a.Z1) + (k0 % a.Z2) + 4 * c4);
-          v = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
-        }
-        bw_reg[q] = v;
-        bw_sgn[q] = sg;
+      for (int q = 0; q < DX_LOADS; ++q) {
+        const int e = kt + dx_ent[q];
+        const float* src = p.M + s_off[e] + dx_rowoff[q] + kin;
+        const f4u m0v = *reinterpret_cast<const f4u*>(src);
+        const f4u m1v = *reinterpret_cast<const f4u*>(src + 4);
+        dx_reg[2 * q] = floatx4{m0v.v[0], m0v.v[1], m0v.v[2], m0v.v[3]};
+        dx_reg[2 * q + 1] = floatx4{m1v.v[0], m1v.v[1], m1v.v[2], m1v.v[3]};
+        dx_sgn[q] = s_sgn[e];
       }
     } else {
-      constexpr int CPR = BN / 8, RPP = 256 / CPR;
-      const int c = tid % CPR, r0 = tid / CPR;
-#pragma unroll
-      for (int q = 0; q < BD_LOADS; ++q) {
-        const int kr = r0 + RPP * q;
-        uint4v v = {0u, 0u, 0u, 0u};
-        if (k0 + kr < k_end && n0 + 8 * c < (int)a.O)
-          v = *reinterpret_cast<const uint4v*>(p.B + (int64_t)(k0 + kr) * p.ldb + n0 + 8 * c);
-        bd_reg[q] = v;
-      }
+      ta.load(p.A, p.lda, k0, I - 1, ta_col, t_kb);
+      tb.load(p.B, p.ldb, k0, I - 1, tb_col, t_kb);
     }
   };
 
-  auto store_lds = [&](int stage) {
-    char* At = smem + stage * STAGE;
-    char* Bt = At + A_BYTES;
-    if (A_KMAJ) {
-      const int c = tid & 7, r0 = tid >> 3;
+  auto store_lds = [&](int step) {
+    const int k0 = k_begin + step * BK;
+#ifdef ROAST_EXP_NOLDSW
+    if (step > 0) return;
+#endif
+    if (MODE != MODE_DM) {
 #pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) *reinterpret_cast<uint4v*>(At + kmaj_off(r0 + 32 * q, c)) = a_reg[q];
-    } else {
-      constexpr int CPR = BM / 8, RPP = 256 / CPR;
-      const int c = tid % CPR, r0 = tid / CPR;
-#pragma unroll
-      for (int q = 0; q < A_LOADS; ++q)
-        *reinterpret_cast<uint4v*>(At + (r0 + RPP * q) * A_STRIDE + c * 16) = a_reg[q];
+      for (int q = 0; q < A_LOADS; ++q) *reinterpret_cast<uint4v*>(At + lds_off((tid >> 3) + 32 * q, tid & 7)) = a_reg[q];
     }
     if (MODE == MODE_FWD) {
-      constexpr int CPR = BN / 4, RPP = 256 / CPR;
-      const int c4 = tid % CPR, r0 = tid / CPR;
+      const float sg = fw_sgn;
 #pragma unroll
-      for (int q = 0; q < BW_LOADS; ++q) {
-        const floatx4 v = bw_reg[q];
-        uint2v w = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
-        *reinterpret_cast<uint2v*>(Bt + (r0 + RPP * q) * B_STRIDE + c4 * 8) = w;
-      }
+      for (int b = 0; b < FW_BLK; ++b)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          uint4v o;
+#pragma unroll
+          for (int pr = 0; pr < 4; ++pr)
+            o[pr] = pack_bf16x2(fw_reg[b * 8 + 2 * pr][c] * sg, fw_reg[b * 8 + 2 * pr + 1][c] * sg);
+          *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (tid % FW_NG) + c, tid / FW_NG + FW_KBS * b)) = o;
+        }
     } else if (MODE == MODE_DX) {
-      const int c4 = tid & 15, r0 = tid >> 4;
 #pragma unroll
-      for (int q = 0; q < BW_LOADS; ++q) {
-        const floatx4 v = bw_reg[q];
-        const float sg = bw_sgn[q];
-        uint2v w = {pack_bf16x2(v[0] * sg, v[1] * sg), pack_bf16x2(v[2] * sg, v[3] * sg)};
-        *reinterpret_cast<uint2v*>(Bt + kmaj_off(r0 + 16 * q, c4 >> 1) + 8 * (c4 & 1)) = w;
+      for (int q = 0; q < DX_LOADS; ++q) {
+        const floatx4 u = dx_reg[2 * q], v = dx_reg[2 * q + 1];
+        const float sg = dx_sgn[q];
+        uint4v o = {pack_bf16x2(u[0] * sg, u[1] * sg), pack_bf16x2(u[2] * sg, u[3] * sg),
+                    pack_bf16x2(v[0] * sg, v[1] * sg), pack_bf16x2(v[2] * sg, v[3] * sg)};
+        *reinterpret_cast<uint4v*>(Bt + lds_off((tid >> 3) + 32 * q, tid & 7)) = o;
       }
     } else {
-      constexpr int CPR = BN / 8, RPP = 256 / CPR;
-      const int c = tid % CPR, r0 = tid / CPR;
-#pragma unroll
-      for (int q = 0; q < BD_LOADS; ++q)
-        *reinterpret_cast<uint4v*>(Bt + (r0 + RPP * q) * B_STRIDE + c * 16) = bd_reg[q];
+      ta.store(At, k0, k_end, t_blk, t_kb);
+      tb.store(Bt, k0, k_end, t_blk, t_kb);
     }
   };
 
@@ -287,65 +296,79 @@ __global__ __launch_bounds__(256, 1) void k_roast_mfma(KernArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  auto compute = [&](int stage) {
-    const char* At = smem + stage * STAGE;
-    const char* Bt = At + A_BYTES;
+  // FWD / DX issue the MFMA with the operands swapped (weight fragment first), so that a lane ends
+  // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
+  auto compute = [&]() {
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
       bf16x8 af[MI], bfr[NI];
 #pragma unroll
-      for (int i = 0; i < MI; ++i) {
-        const int r = wm * (BM / 2) + i * 32;
-        af[i] = A_KMAJ ? frag_kmaj(At, r, ks, lane) : frag_mmaj<A_STRIDE>(At, r, ks, lane);
-      }
+      for (int i = 0; i < MI; ++i) af[i] = frag(At, wm * WTM + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const int c = wn * (BN / 2) + j * 32;
-        bfr[j] = B_KMAJ ? frag_kmaj(Bt, c, ks, lane) : frag_mmaj<B_STRIDE>(Bt, c, ks, lane);
-      }
+      for (int j = 0; j < NI; ++j) bfr[j] = frag(Bt, wn * WTN + j * 32, ks, lane);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NI; ++j) {
+#ifdef ROAST_EXP_NOMFMA
+          if (i != 0 || j != 0) continue;
+#endif
+          if (MODE == MODE_DM)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
     }
   };
 
-  if (nsteps > 0) {
-    load_global(0);
-    store_lds(0);
-  }
-  __syncthreads();
+  if (nsteps > 0) load_global(0);
   for (int s = 0; s < nsteps; ++s) {
-    const bool more = s + 1 < nsteps;
-    if (more) load_global(s + 1);
-    compute(s & 1);
-    if (more) store_lds((s + 1) & 1);
+    store_lds(s);
+    __syncthreads();
+    if (s + 1 < nsteps) load_global(s + 1);
+    compute();
     __syncthreads();
   }
 
-  // ---- epilogue.  acc[i][j][e]: row = 8*(e/4) + 4*(lane/32) + e%4, col = lane%32 inside the block.
-  const int lr = 4 * (lane >> 5), lc = lane & 31;
+  // ---- epilogue
   if (MODE != MODE_DM) {
+    // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
+    // Each wave stages one 32-row block at a time in its own LDS buffer (aliasing the operand tiles,
+    // which are dead after the last barrier) and writes it out 16 bytes per lane.
+    char* ebuf = smem + wave * (32 * EPI_STRIDE);
+    constexpr int CPR = WTN / 8;              // 16-byte chunks per row of the wave tile
+    constexpr int RPI = 64 / CPR;             // rows per store instruction
 #pragma unroll
-    for (int i = 0; i < MI; ++i)
+    for (int i = 0; i < MI; ++i) {
 #pragma unroll
-      for (int j = 0; j < NI; ++j) {
-        const int col = n0 + wn * (BN / 2) + j * 32 + lc;
+      for (int j = 0; j < NI; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (e >> 2) + lr + (e & 3);
-          if (row < Mdim && col < Ndim)
-            p.C[(int64_t)row * p.ldc + col] = __builtin_bit_cast(uint16_t, (__bf16)(a.lambda * acc[i][j][e]));
+        for (int q = 0; q < 4; ++q) {
+          uint2v w = {pack_bf16x2(a.lambda * acc[i][j][4 * q], a.lambda * acc[i][j][4 * q + 1]),
+                      pack_bf16x2(a.lambda * acc[i][j][4 * q + 2], a.lambda * acc[i][j][4 * q + 3])};
+          *reinterpret_cast<uint2v*>(ebuf + (lane & 31) * EPI_STRIDE + (j * 32 + 8 * q + 4 * (lane >> 5)) * 2) = w;
         }
+      // same wave wrote and reads: LDS operations of one wave complete in order
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int r = it * RPI + lane / CPR, c = lane % CPR;
+        const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + c * 16);
+        const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + c * 8;
+#ifdef ROAST_EXP_NOSTORE
+        if (v[0] == 0x12345678u)
+#endif
+        if (row < Mdim && col < Ndim) *reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col) = v;
       }
+    }
   } else {
+    // acc[i][j][e]: row (h) = 8*(e/4) + 4*(lane >> 5) + e%4, column (o) = lane & 31 inside the block
+    const int lr = 4 * (lane >> 5), lc = lane & 31;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        const int hb = m0 + wm * (BM / 2) + i * 32;      // block origin: inside one hash tile (Z1, Z2 % 32 == 0)
-        const int ob = n0 + wn * (BN / 2) + j * 32;
+        const int hb = m0 + wm * WTM + i * 32;      // block origin: inside one hash tile (Z1, Z2 % 32 == 0)
+        const int ob = n0 + wn * WTN + j * 32;
         if (hb >= (int)a.H || ob >= (int)a.O) continue;
         if (p.G) {
           float* g = p.G + ((int64_t)blockIdx.z * a.H + hb) * a.O + ob + lc;
@@ -361,6 +384,9 @@ __global__ __launch_bounds__(256, 1) void k_roast_mfma(KernArgs p) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int r = 8 * (e >> 2) + lr + (e & 3);
+#ifdef ROAST_EXP_NOSTORE
+            if (acc[i][j][e] == 1234567.f)
+#endif
             if (hb + r < (int)a.H && ob + lc < (int)a.O) unsafeAtomicAdd(d + (int64_t)r * a.Z2, sc * acc[i][j][e]);
           }
         }
@@ -368,24 +394,20 @@ __global__ __launch_bounds__(256, 1) void k_roast_mfma(KernArgs p) {
   }
 }
 
-template <int MODE, int BM, int BN>
-constexpr int smem_bytes() {
-  constexpr int A_BYTES = (MODE != MODE_DM) ? KMaj<BM>::kBytes : MMaj<BM>::kBytes;
-  constexpr int B_BYTES = (MODE == MODE_DX) ? KMaj<BN>::kBytes : MMaj<BN>::kBytes;
-  return 2 * (A_BYTES + B_BYTES) + kMaxTable * 12;
-}
+template <int BM, int BN>
+constexpr int smem_bytes() { return (BM + BN) * 128 + kMaxTable * 12; }
 
-template <int MODE, int BM, int BN>
+template <int MODE, int BM, int BN, int WGM, int WGN>
 roast_status launch(const KernArgs& p, dim3 grid, hipStream_t s) {
-  constexpr int smem = smem_bytes<MODE, BM, BN>();
+  constexpr int smem = smem_bytes<BM, BN>();
   static bool configured = false;   // one attribute call per instantiation per process
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN>), grid, dim3(256), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN>), grid, dim3(256), smem, s, p);
   return hip_status(hipGetLastError());
 }
 
@@ -396,40 +418,43 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy,
                          hipStream_t s) {
-  if (a.Z1 % BK != 0 || a.H % a.Z1 != 0 || a.Z2 % 4 != 0 || a.O % 4 != 0 || ldx % 8 != 0 || !aligned16(X))
+  if (a.Z1 % BK != 0 || a.H % a.Z1 != 0 || a.Z2 % 4 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
+      !aligned16(X) || !aligned16(Y))
     return ROAST_ERR_UNSUPPORTED;
-  constexpr int BM = 256, BN = 256;
-  if (a.nTx * cdiv(BN, a.Z2) + a.nTx > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  constexpr int BM = 256, BN = 128;
+  if (a.nTx * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.C = (uint16_t*)Y; p.ldc = ldy;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
   if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_FWD, BM, BN>(p, grid, s);
+  return launch<MODE_FWD, BM, BN, 2, 2>(p, grid, s);
 }
 
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx,
                             hipStream_t s) {
-  if (a.Z2 % BK != 0 || a.O % a.Z2 != 0 || ldy % 8 != 0 || !aligned16(dY)) return ROAST_ERR_UNSUPPORTED;
-  constexpr int BM = 256, BN = 256;
-  if (a.nTy * cdiv(BN, a.Z1) + a.nTy > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  if (a.Z2 % BK != 0 || a.O % a.Z2 != 0 || a.H % 8 != 0 || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) ||
+      !aligned16(dX))
+    return ROAST_ERR_UNSUPPORTED;
+  constexpr int BM = 256, BN = 128;
+  if (a.nTy * (cdiv(BN, a.Z1) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.C = (uint16_t*)dX; p.ldc = ldx;
   const dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_DX, BM, BN>(p, grid, s);
+  return launch<MODE_DX, BM, BN, 2, 2>(p, grid, s);
 }
 
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
                             float* Gws, int splits, hipStream_t s) {
+  constexpr int BM = 256, BN = 128;
   if (a.Z1 % 32 != 0 || a.Z2 % 32 != 0 || a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
-      !aligned16(X) || !aligned16(dY))
+      !aligned16(X) || !aligned16(dY) || a.H < BM / 32 || a.O < BN / 32)
     return ROAST_ERR_UNSUPPORTED;
-  constexpr int BM = 256, BN = 256;
-  if (cdiv(BM, a.Z1) * cdiv(BN, a.Z2) + cdiv(BM, a.Z1) + cdiv(BN, a.Z2) + 1 > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  if ((cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   const int64_t tiles = cdiv(a.H, BM) * cdiv(a.O, BN);
   if (Gws == nullptr) {
-    // enough workgroups to fill 256 CUs a few times over, but at least 4 contraction steps each
-    int64_t want = cdiv(768, tiles);
+    // enough workgroups to fill 256 CUs twice over, but at least 4 contraction steps each
+    int64_t want = cdiv(512, tiles);
     const int64_t cap = cdiv(a.I, 4 * BK);
     if (want > cap) want = cap;
     if (want < 1) want = 1;
@@ -443,7 +468,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   p.rows_per_split = (int)rows;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
   if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_DM, BM, BN>(p, grid, s);
+  return launch<MODE_DM, BM, BN, 2, 2>(p, grid, s);
 }
 
 }  // namespace roast
