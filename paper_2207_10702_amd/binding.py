@@ -52,10 +52,11 @@ def load() -> C.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
+    path = os.environ.get("ROAST_HIP_LIB", LIB_PATH)     # override: point at another build of the same library
+    if path == LIB_PATH and not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build()
-    lib = C.CDLL(LIB_PATH)
+    lib = C.CDLL(path)
     vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
     MP, EP = C.POINTER(RoastMMDesc), C.POINTER(RoastEmbedDesc)
     lib.roast_status_string.argtypes = [i32]

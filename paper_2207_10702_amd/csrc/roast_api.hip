@@ -170,8 +170,8 @@ roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t
 size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_reduce_mode mode) {
   EmbedArgs a;
   if (make_embed_args(d, N, &a) != ROAST_OK) return 0;
-  if (mode != ROAST_REDUCE_DETERMINISTIC || N == 0) return 0;
-  return embed_det_workspace_bytes(a);
+  if (N == 0) return 0;
+  return mode == ROAST_REDUCE_DETERMINISTIC ? embed_det_workspace_bytes(a) : embed_bucket_workspace_bytes(a);
 }
 
 roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t* rows, const uint32_t* table_ids,
@@ -189,7 +189,7 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
     if (!ws || ws_bytes < need) return ROAST_ERR_WORKSPACE;
     return embed_bwd_det_run(a, rows, table_ids, dOut, dM, ws, (hipStream_t)stream);
   }
-  return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, (hipStream_t)stream);
+  return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, ws, ws_bytes, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -48,6 +48,7 @@ struct HashDev {
   uint64_t s0, s1, s2, s3;
   uint32_t align;
   uint32_t use_sign;
+  uint32_t slots_mu32;  // floor(2^32 / slots) when slots < 2^32 (0 otherwise: then u mod slots == u)
 };
 
 // block = scalars per block (Z1*Z2 or Z).  Caller has validated m_size >= block, align >= 1.
@@ -59,6 +60,7 @@ inline HashDev make_hash_dev(const roast_hash& h, int64_t m_size, int64_t block)
   d.s0 = h.s0; d.s1 = h.s1; d.s2 = h.s2; d.s3 = h.s3;
   d.align = h.align;
   d.use_sign = h.use_sign;
+  d.slots_mu32 = d.slots.d < (1ull << 32) ? (d.slots.d <= 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / d.slots.d)) : 0u;
   return d;
 }
 
@@ -83,5 +85,60 @@ __host__ __device__ inline int block_sign(const HashDev& h, uint64_t k0, uint64_
   uint64_t v = cw(h.P, h.s0, h.s1, h.s2, h.s3, k0, k1, k2);
   return 1 - 2 * (int)(v & 1ull);
 }
+
+// ---- the same map evaluated incrementally over the last key (used by the lookup kernels, where one
+// row has several chunks k2 = 0, 1, 2, ...).  RowHash holds the part that does not depend on k2.
+struct RowHash {
+  uint32_t u;  // (a0*k0 + a1*k1 + a3) mod P
+  uint32_t v;  // (s0*k0 + s1*k1 + s3) mod P
+};
+
+__host__ __device__ inline RowHash row_hash(const HashDev& h, uint64_t k0, uint64_t k1) {
+  const uint64_t r0 = bmod(k0, h.P), r1 = bmod(k1, h.P);
+  RowHash r;
+  r.u = (uint32_t)bmod(bmod(h.a0 * r0, h.P) + bmod(h.a1 * r1, h.P) + h.a3, h.P);
+  r.v = h.use_sign ? (uint32_t)bmod(bmod(h.s0 * r0, h.P) + bmod(h.s1 * r1, h.P) + h.s3, h.P) : 0u;
+  return r;
+}
+
+// u mod slots for u < P < 2^32, by a 32-bit Barrett step (or the identity when slots >= 2^32).
+__host__ __device__ inline uint32_t mod_slots32(const HashDev& h, uint32_t u) {
+  if (h.slots.d >= (1ull << 32)) return u;
+  const uint32_t d = (uint32_t)h.slots.d;
+#if defined(__HIP_DEVICE_COMPILE__)
+  const uint32_t q = __umulhi(u, h.slots_mu32);
+#else
+  const uint32_t q = (uint32_t)(((uint64_t)u * h.slots_mu32) >> 32);
+#endif
+  uint32_t r = u - q * d;
+  if (r >= d) r -= d;
+  if (r >= d) r -= d;      // slots == 1: mu32 saturates and the estimate can be two short
+  return r;
+}
+
+// Walks k2 = 0, 1, 2, ... for one row: t2 = (a2*k2) mod P and ts = (s2*k2) mod P are advanced by
+// one add and one conditional subtract per step.  Valid while k2 < P (the caller checks C <= P).
+struct ChunkWalk {
+  uint32_t t2, ts;
+  __host__ __device__ ChunkWalk() : t2(0u), ts(0u) {}
+  __host__ __device__ inline void get(const HashDev& h, const RowHash& r, int64_t* off, int* sgn) const {
+    const uint32_t P = (uint32_t)h.P.d;
+    uint64_t u = (uint64_t)r.u + t2;
+    if (u >= P) u -= P;
+    *off = (int64_t)((uint64_t)h.align * mod_slots32(h, (uint32_t)u));
+    uint64_t v = (uint64_t)r.v + ts;
+    if (v >= P) v -= P;
+    *sgn = h.use_sign ? 1 - 2 * (int)(v & 1ull) : 1;
+  }
+  __host__ __device__ inline void next(const HashDev& h) {
+    const uint32_t P = (uint32_t)h.P.d;
+    uint64_t a = (uint64_t)t2 + h.a2;
+    if (a >= P) a -= P;
+    t2 = (uint32_t)a;
+    uint64_t b = (uint64_t)ts + h.s2;
+    if (b >= P) b -= P;
+    ts = (uint32_t)b;
+  }
+};
 
 }  // namespace roast

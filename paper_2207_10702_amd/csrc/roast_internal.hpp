@@ -78,8 +78,10 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
 // ---- lookup kernels (roast_embed.hip)
 roast_status embed_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
                               float* out, hipStream_t s);
+// ws may be null (or too small): the gradient then goes straight to dM with global atomics.
+size_t embed_bucket_workspace_bytes(const EmbedArgs& a);
 roast_status embed_bwd_atomic_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables,
-                                     const float* dOut, float* dM, hipStream_t s);
+                                     const float* dOut, float* dM, void* ws, size_t ws_bytes, hipStream_t s);
 size_t embed_det_workspace_bytes(const EmbedArgs& a);
 roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
                                float* dM, void* ws, hipStream_t s);

@@ -2,11 +2,14 @@
 // arXiv 2207.10702): forward Y = X*W, dX = dY*W^T and the per-tile products of dM = scatter(X^T*dY),
 // with W recovered from M tile by tile and never written to memory.
 //
-// One workgroup = 256 threads = 4 waves (WGM x WGN) computes a BM x BN block of the output with
-// v_mfma_f32_32x32x16_bf16; each wave owns a (BM/WGM) x (BN/WGN) sub-block in fp32 accumulators.
-// The contraction runs in steps of BK = 64: the next step's operands are fetched from global
-// memory into registers while the MFMAs of the current step read LDS, then written to LDS between
-// two barriers.  Two workgroups share a CU, so one computes while the other moves data.
+// One workgroup = 512 threads = 8 waves computes a BM x BN block of the output.  The waves are
+// specialised: waves 0-3 (WGM x WGN) are consumers, each owning a (BM/WGM) x (BN/WGN) sub-block in
+// fp32 accumulators and doing nothing but ds_read_b128 + v_mfma_f32_32x32x16_bf16; waves 4-7 are
+// producers that fetch the next operands from global memory into registers (two register sets,
+// i.e. two contraction steps ahead), sign / round / transpose them and fill the other LDS stage.
+// Each SIMD then holds one consumer and one producer wave, and the hardware interleaves the
+// producer's VMEM / VALU / LDS-write instructions between the consumer's MFMAs.  The contraction
+// runs in steps of BK = 64 through two LDS stages with one workgroup barrier per step.
 //
 // Both operands sit in LDS as [row][k] with 128-byte rows whose 16-byte chunks are XOR-swizzled,
 // so a lane fetches the 8 contraction values of its row with one conflict-free ds_read_b128
@@ -112,23 +115,54 @@ struct TLoad {
   }
 };
 
+// ---------------------------------------------------------------------------------------------
+// Producer side: per-thread addressing context and one register set of staged operand data.
+template <int MODE, int BM, int BN>
+struct ProdCtx {
+  static constexpr int A_LOADS = BM / 32;
+  static constexpr int FW_NG = BN / 4, FW_KBS = 256 / FW_NG, FW_BLK = 8 / FW_KBS;
+  static constexpr int DX_LOADS = BN / 32;
+  int ptid;
+  // FWD / DX, A operand: BM rows x 8 chunks; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
+  const uint16_t* a_ptr[MODE == MODE_DM ? 1 : A_LOADS];
+  // FWD, B operand: 8(k) x 4(n) fp32 blocks; thread -> column group ptid % FW_NG, k-blocks ptid / FW_NG + FW_KBS*b
+  int fw_yl, fw_nin;
+  // DX, B operand: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
+  int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
+  int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
+  // DM: 8(k) x CW blocks of both operands; thread -> column block ptid & 31, k-block ptid >> 5
+  int ta_col, tb_col;
+};
+
+template <int MODE, int BM, int BN>
+struct RegSet {
+  using Ctx = ProdCtx<MODE, BM, BN>;
+  uint4v a_reg[MODE == MODE_DM ? 1 : Ctx::A_LOADS];
+  floatx4 fw_reg[MODE == MODE_FWD ? Ctx::FW_BLK * 8 : 1];
+  float fw_sgn;
+  floatx4 dx_reg[MODE == MODE_DX ? Ctx::DX_LOADS * 2 : 1];
+  float dx_sgn[MODE == MODE_DX ? Ctx::DX_LOADS : 1];
+  TLoad<MODE == MODE_DM ? BM : 128> ta;
+  TLoad<MODE == MODE_DM ? BN : 128> tb;
+};
+
 template <int MODE, int BM, int BN, int WGM, int WGN>
-__global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
-  static_assert(WGM * WGN == 4, "4 waves");
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wave tile
+__global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
+  static_assert(WGM * WGN == 4, "4 consumer waves");
+  using Ctx = ProdCtx<MODE, BM, BN>;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;  // consumer wave tile
   constexpr int MI = WTM / 32, NI = WTN / 32;    // 32x32 blocks per wave
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
   constexpr int EPI_STRIDE = WTN * 2 + 16;       // bytes per row of a wave's epilogue buffer
+  constexpr int EPI_BYTES = 4 * 32 * EPI_STRIDE;
 
   extern __shared__ __attribute__((aligned(128))) char smem[];
-  char* At = smem;
-  char* Bt = smem + A_BYTES;
-  int64_t* s_off = reinterpret_cast<int64_t*>(smem + A_BYTES + B_BYTES);
-  float* s_sgn = reinterpret_cast<float*>(smem + A_BYTES + B_BYTES + kMaxTable * 8);
+  int64_t* s_off = reinterpret_cast<int64_t*>(smem + 2 * STAGE + EPI_BYTES);
+  float* s_sgn = reinterpret_cast<float*>(smem + 2 * STAGE + EPI_BYTES + kMaxTable * 8);
 
   const MMArgs& a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
+  const bool producer = wave >= 4;
   const int I = (int)a.I;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int Mdim = MODE == MODE_DM ? (int)a.H : I;
@@ -138,9 +172,9 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
     k_begin = blockIdx.z * p.rows_per_split;
     k_end = min(I, k_begin + p.rows_per_split);
   }
-  const int nsteps = (k_end - k_begin + BK - 1) / BK;
+  const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
 
-  // ---- tile table
+  // ---- tile table (all 512 threads)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
   // DX : entry [kt * TN + xl] for tile (x = n0/Z1 + xl, y = kt), TN = tiles spanned by BN along H
   // DM : entry [xl * TN + yl] for tile (x = m0/Z1 + xl, y = n0/Z2 + yl)
@@ -160,7 +194,7 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
       TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
       cnt = ((min(m0 + BM, (int)a.H) - 1) / a.Z1 - x0 + 1) * TN;
     }
-    for (int e = tid; e < cnt; e += 256) {
+    for (int e = tid; e < cnt; e += 512) {
       uint64_t x, y;
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
       else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
@@ -171,123 +205,148 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
   }
   __syncthreads();
 
-  // ---- operand staging.  Loads are unconditional: rows / columns outside the problem are
-  // redirected to a valid address and their products are never stored; only the contraction tail
-  // of the dM product is zeroed.
-  // A operand, FWD / DX: BM rows x 8 chunks, thread -> chunk (tid & 7) of rows (tid >> 3) + 32*q
-  constexpr int A_LOADS = BM / 32;
-  uint4v a_reg[MODE == MODE_DM ? 1 : A_LOADS];
-  const uint16_t* a_ptr[MODE == MODE_DM ? 1 : A_LOADS];
-  if (MODE != MODE_DM) {
+  if (producer) {
+    // =========================================================================== producer waves
+    // Loads are unconditional: rows / columns outside the problem are redirected to a valid address
+    // and their products are never stored; only the contraction tail of the dM product is zeroed.
+    Ctx c;
+    c.ptid = tid - 256;
+    const int pt = c.ptid;
+    if (MODE != MODE_DM) {
 #pragma unroll
-    for (int q = 0; q < A_LOADS; ++q)
-      a_ptr[q] = p.A + (int64_t)min(m0 + (tid >> 3) + 32 * q, I - 1) * p.lda + 8 * (tid & 7);
-  }
-  // B operand, FWD: 8(k) x 4(n) fp32 blocks; thread -> column group (tid % (BN/4)), k-blocks kb + KBS*q
-  constexpr int FW_NG = BN / 4, FW_KBS = 256 / FW_NG, FW_BLK = 8 / FW_KBS;
-  floatx4 fw_reg[MODE == MODE_FWD ? FW_BLK * 8 : 1];
-  int fw_yl = 0, fw_nin = 0;
-  float fw_sgn = 1.f;
-  if (MODE == MODE_FWD) {
-    const int n = min(n0 + 4 * (tid % FW_NG), (int)a.O - 4);
-    fw_yl = n / a.Z2 - n0 / a.Z2;
-    fw_nin = n % a.Z2;
-  }
-  // B operand, DX: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (tid & 7) of rows (tid >> 3) + 32*q
-  constexpr int DX_LOADS = BN / 32;
-  floatx4 dx_reg[MODE == MODE_DX ? DX_LOADS * 2 : 1];
-  float dx_sgn[MODE == MODE_DX ? DX_LOADS : 1];
-  int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
-  int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
-  if (MODE == MODE_DX) {
-#pragma unroll
-    for (int q = 0; q < DX_LOADS; ++q) {
-      const int h = min(n0 + (tid >> 3) + 32 * q, (int)a.H - 1);
-      dx_ent[q] = h / a.Z1 - n0 / a.Z1;
-      dx_rowoff[q] = a.Z2 * (h % a.Z1) + 8 * (tid & 7);
+      for (int q = 0; q < Ctx::A_LOADS; ++q)
+        c.a_ptr[q] = p.A + (int64_t)min(m0 + (pt >> 3) + 32 * q, I - 1) * p.lda + 8 * (pt & 7);
     }
-  }
-  // DM: both operands transposed
-  TLoad<MODE == MODE_DM ? BM : 128> ta;
-  TLoad<MODE == MODE_DM ? BN : 128> tb;
-  const int t_blk = tid & 31, t_kb = tid >> 5;
-  const int ta_col = min(m0 + t_blk * (BM / 32), (int)a.H - BM / 32);
-  const int tb_col = min(n0 + t_blk * (BN / 32), (int)a.O - BN / 32);
+    if (MODE == MODE_FWD) {
+      const int n = min(n0 + 4 * (pt % Ctx::FW_NG), (int)a.O - 4);
+      c.fw_yl = n / a.Z2 - n0 / a.Z2;
+      c.fw_nin = n % a.Z2;
+    }
+    if (MODE == MODE_DX) {
+#pragma unroll
+      for (int q = 0; q < Ctx::DX_LOADS; ++q) {
+        const int h = min(n0 + (pt >> 3) + 32 * q, (int)a.H - 1);
+        c.dx_ent[q] = h / a.Z1 - n0 / a.Z1;
+        c.dx_rowoff[q] = a.Z2 * (h % a.Z1) + 8 * (pt & 7);
+      }
+    }
+    if (MODE == MODE_DM) {
+      c.ta_col = min(m0 + (pt & 31) * (BM / 32), (int)a.H - BM / 32);
+      c.tb_col = min(n0 + (pt & 31) * (BN / 32), (int)a.O - BN / 32);
+    }
 
-  auto load_global = [&](int step) {
-    const int k0 = k_begin + step * BK;
+    auto load_global = [&](RegSet<MODE, BM, BN>& r, int step) {
+      const int k0 = k_begin + step * BK;
 #ifdef ROAST_EXP_NOLOAD
-    if (step > 0) return;
+      if (step > 1) return;
 #endif
-    if (MODE != MODE_DM) {
+      if (MODE != MODE_DM) {
 #pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) a_reg[q] = *reinterpret_cast<const uint4v*>(a_ptr[q] + k0);
-    }
-    if (MODE == MODE_FWD) {
-      const int e = (k0 / a.Z1) * TN + fw_yl;
-      const float* base = p.M + s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (tid / FW_NG)) + fw_nin;
-      fw_sgn = s_sgn[e];
-#pragma unroll
-      for (int b = 0; b < FW_BLK; ++b)
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const f4u m = *reinterpret_cast<const f4u*>(base + (int64_t)(8 * FW_KBS * b + r) * a.Z2);
-          fw_reg[b * 8 + r] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
-        }
-    } else if (MODE == MODE_DX) {
-      const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
-#pragma unroll
-      for (int q = 0; q < DX_LOADS; ++q) {
-        const int e = kt + dx_ent[q];
-        const float* src = p.M + s_off[e] + dx_rowoff[q] + kin;
-        const f4u m0v = *reinterpret_cast<const f4u*>(src);
-        const f4u m1v = *reinterpret_cast<const f4u*>(src + 4);
-        dx_reg[2 * q] = floatx4{m0v.v[0], m0v.v[1], m0v.v[2], m0v.v[3]};
-        dx_reg[2 * q + 1] = floatx4{m1v.v[0], m1v.v[1], m1v.v[2], m1v.v[3]};
-        dx_sgn[q] = s_sgn[e];
+        for (int q = 0; q < Ctx::A_LOADS; ++q) r.a_reg[q] = *reinterpret_cast<const uint4v*>(c.a_ptr[q] + k0);
       }
-    } else {
-      ta.load(p.A, p.lda, k0, I - 1, ta_col, t_kb);
-      tb.load(p.B, p.ldb, k0, I - 1, tb_col, t_kb);
-    }
-  };
+      // Keep the issue order of the load groups the same everywhere (prologue and loop): the wait
+      // counters are in-order, and a differing order would make the waits before the LDS writes
+      // cover the newest loads as well.
+      __builtin_amdgcn_sched_barrier(0);
+      if (MODE == MODE_FWD) {
+        const int e = (k0 / a.Z1) * TN + c.fw_yl;
+        const float* base = p.M + s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (pt / Ctx::FW_NG)) + c.fw_nin;
+        r.fw_sgn = s_sgn[e];
+#pragma unroll
+        for (int b = 0; b < Ctx::FW_BLK; ++b)
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const f4u m = *reinterpret_cast<const f4u*>(base + (int64_t)(8 * Ctx::FW_KBS * b + q) * a.Z2);
+            r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
+          }
+      } else if (MODE == MODE_DX) {
+        const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
+#pragma unroll
+        for (int q = 0; q < Ctx::DX_LOADS; ++q) {
+          const int e = kt + c.dx_ent[q];
+          const float* src = p.M + s_off[e] + c.dx_rowoff[q] + kin;
+          const f4u m0v = *reinterpret_cast<const f4u*>(src);
+          const f4u m1v = *reinterpret_cast<const f4u*>(src + 4);
+          r.dx_reg[2 * q] = floatx4{m0v.v[0], m0v.v[1], m0v.v[2], m0v.v[3]};
+          r.dx_reg[2 * q + 1] = floatx4{m1v.v[0], m1v.v[1], m1v.v[2], m1v.v[3]};
+          r.dx_sgn[q] = s_sgn[e];
+        }
+      } else if (MODE == MODE_DM) {
+        r.ta.load(p.A, p.lda, k0, I - 1, c.ta_col, pt >> 5);
+        __builtin_amdgcn_sched_barrier(0);
+        r.tb.load(p.B, p.ldb, k0, I - 1, c.tb_col, pt >> 5);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
 
-  auto store_lds = [&](int step) {
-    const int k0 = k_begin + step * BK;
+    auto store_lds = [&](RegSet<MODE, BM, BN>& r, int step) {
+      const int k0 = k_begin + step * BK;
 #ifdef ROAST_EXP_NOLDSW
-    if (step > 0) return;
+      if (step > 1) return;
 #endif
-    if (MODE != MODE_DM) {
+      char* At = smem + (step & 1) * STAGE;
+      char* Bt = At + A_BYTES;
+      if (MODE != MODE_DM) {
 #pragma unroll
-      for (int q = 0; q < A_LOADS; ++q) *reinterpret_cast<uint4v*>(At + lds_off((tid >> 3) + 32 * q, tid & 7)) = a_reg[q];
-    }
-    if (MODE == MODE_FWD) {
-      const float sg = fw_sgn;
-#pragma unroll
-      for (int b = 0; b < FW_BLK; ++b)
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          uint4v o;
-#pragma unroll
-          for (int pr = 0; pr < 4; ++pr)
-            o[pr] = pack_bf16x2(fw_reg[b * 8 + 2 * pr][c] * sg, fw_reg[b * 8 + 2 * pr + 1][c] * sg);
-          *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (tid % FW_NG) + c, tid / FW_NG + FW_KBS * b)) = o;
-        }
-    } else if (MODE == MODE_DX) {
-#pragma unroll
-      for (int q = 0; q < DX_LOADS; ++q) {
-        const floatx4 u = dx_reg[2 * q], v = dx_reg[2 * q + 1];
-        const float sg = dx_sgn[q];
-        uint4v o = {pack_bf16x2(u[0] * sg, u[1] * sg), pack_bf16x2(u[2] * sg, u[3] * sg),
-                    pack_bf16x2(v[0] * sg, v[1] * sg), pack_bf16x2(v[2] * sg, v[3] * sg)};
-        *reinterpret_cast<uint4v*>(Bt + lds_off((tid >> 3) + 32 * q, tid & 7)) = o;
+        for (int q = 0; q < Ctx::A_LOADS; ++q)
+          *reinterpret_cast<uint4v*>(At + lds_off((pt >> 3) + 32 * q, pt & 7)) = r.a_reg[q];
       }
-    } else {
-      ta.store(At, k0, k_end, t_blk, t_kb);
-      tb.store(Bt, k0, k_end, t_blk, t_kb);
-    }
-  };
+      if (MODE == MODE_FWD) {
+        const float sg = r.fw_sgn;
+#pragma unroll
+        for (int b = 0; b < Ctx::FW_BLK; ++b)
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) {
+            uint4v o;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr)
+              o[pr] = pack_bf16x2(r.fw_reg[b * 8 + 2 * pr][cc] * sg, r.fw_reg[b * 8 + 2 * pr + 1][cc] * sg);
+            *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (pt % Ctx::FW_NG) + cc, pt / Ctx::FW_NG + Ctx::FW_KBS * b)) = o;
+          }
+      } else if (MODE == MODE_DX) {
+#pragma unroll
+        for (int q = 0; q < Ctx::DX_LOADS; ++q) {
+          const floatx4 u = r.dx_reg[2 * q], v = r.dx_reg[2 * q + 1];
+          const float sg = r.dx_sgn[q];
+          uint4v o = {pack_bf16x2(u[0] * sg, u[1] * sg), pack_bf16x2(u[2] * sg, u[3] * sg),
+                      pack_bf16x2(v[0] * sg, v[1] * sg), pack_bf16x2(v[2] * sg, v[3] * sg)};
+          *reinterpret_cast<uint4v*>(Bt + lds_off((pt >> 3) + 32 * q, pt & 7)) = o;
+        }
+      } else if (MODE == MODE_DM) {
+        r.ta.store(At, k0, k_end, pt & 31, pt >> 5);
+        r.tb.store(Bt, k0, k_end, pt & 31, pt >> 5);
+      }
+    };
 
+    // Barrier s publishes stage (s & 1) holding step s.  Filling stage (s & 1) for step s is safe
+    // once barrier s-1 has been passed: the consumers finished reading it (step s-2) before that.
+    // Loads run two steps ahead of their use; the loop body is branch-free (a step index past the
+    // end is clamped and its data never stored) so that the wait for set r0 can leave r1's newer
+    // loads in flight.
+    RegSet<MODE, BM, BN> r0, r1;
+    const int last = nsteps - 1;
+    if (nsteps > 0) {
+      load_global(r0, 0);
+      load_global(r1, min(1, last));
+    }
+    int s = 0;
+    for (; s + 1 < nsteps; s += 2) {
+      store_lds(r0, s);
+      load_global(r0, min(s + 2, last));
+      __syncthreads();                                   // barrier s
+      store_lds(r1, s + 1);
+      load_global(r1, min(s + 3, last));
+      __syncthreads();                                   // barrier s + 1
+    }
+    if (s < nsteps) {                                    // odd number of steps
+      store_lds(r0, s);
+      __syncthreads();
+    }
+    return;
+  }
+
+  // ============================================================================= consumer waves
+  const int wm = wave / WGN, wn = wave % WGN;
   floatx16 acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -298,14 +357,23 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
 
   // FWD / DX issue the MFMA with the operands swapped (weight fragment first), so that a lane ends
   // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
-  auto compute = [&]() {
+  // Fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued.
+  for (int s = 0; s < nsteps; ++s) {
+    __syncthreads();                                     // barrier s: stage (s & 1) holds step s
+    const char* At = smem + (s & 1) * STAGE;
+    const char* Bt = At + A_BYTES;
+    bf16x8 af[2][MI], bfr[2][NI];
+    auto fetch = [&](int ks, int buf) {
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[buf][i] = frag(At, wm * WTM + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[buf][j] = frag(Bt, wn * WTN + j * 32, ks, lane);
+    };
+    fetch(0, 0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[MI], bfr[NI];
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = frag(At, wm * WTM + i * 32, ks, lane);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[j] = frag(Bt, wn * WTN + j * 32, ks, lane);
+      if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -314,28 +382,20 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
           if (i != 0 || j != 0) continue;
 #endif
           if (MODE == MODE_DM)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
           else
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
         }
+      __builtin_amdgcn_sched_barrier(0);
     }
-  };
-
-  if (nsteps > 0) load_global(0);
-  for (int s = 0; s < nsteps; ++s) {
-    store_lds(s);
-    __syncthreads();
-    if (s + 1 < nsteps) load_global(s + 1);
-    compute();
-    __syncthreads();
   }
 
-  // ---- epilogue
+  // ---- epilogue (consumer waves only; the producers have left)
   if (MODE != MODE_DM) {
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
-    // Each wave stages one 32-row block at a time in its own LDS buffer (aliasing the operand tiles,
-    // which are dead after the last barrier) and writes it out 16 bytes per lane.
-    char* ebuf = smem + wave * (32 * EPI_STRIDE);
+    // Each wave stages one 32-row block at a time in its own LDS buffer and writes it out 16 bytes
+    // per lane, row-contiguous.
+    char* ebuf = smem + 2 * STAGE + wave * (32 * EPI_STRIDE);
     constexpr int CPR = WTN / 8;              // 16-byte chunks per row of the wave tile
     constexpr int RPI = 64 / CPR;             // rows per store instruction
 #pragma unroll
@@ -351,9 +411,9 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
       // same wave wrote and reads: LDS operations of one wave complete in order
 #pragma unroll
       for (int it = 0; it < 32 / RPI; ++it) {
-        const int r = it * RPI + lane / CPR, c = lane % CPR;
-        const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + c * 16);
-        const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + c * 8;
+        const int r = it * RPI + lane / CPR, cc = lane % CPR;
+        const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + cc * 16);
+        const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 8;
 #ifdef ROAST_EXP_NOSTORE
         if (v[0] == 0x12345678u)
 #endif
@@ -394,12 +454,13 @@ __global__ __launch_bounds__(256, 2) void k_roast_mfma(KernArgs p) {
   }
 }
 
-template <int BM, int BN>
-constexpr int smem_bytes() { return (BM + BN) * 128 + kMaxTable * 12; }
+template <int BM, int BN, int WGN>
+constexpr int smem_bytes() { return 2 * (BM + BN) * 128 + 4 * 32 * ((BN / WGN) * 2 + 16) + kMaxTable * 12; }
 
 template <int MODE, int BM, int BN, int WGM, int WGN>
 roast_status launch(const KernArgs& p, dim3 grid, hipStream_t s) {
-  constexpr int smem = smem_bytes<BM, BN>();
+  constexpr int smem = smem_bytes<BM, BN, WGN>();
+  static_assert(smem <= 160 * 1024, "LDS budget");
   static bool configured = false;   // one attribute call per instantiation per process
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN>),
@@ -407,7 +468,7 @@ roast_status launch(const KernArgs& p, dim3 grid, hipStream_t s) {
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN>), grid, dim3(256), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN>), grid, dim3(512), smem, s, p);
   return hip_status(hipGetLastError());
 }
 

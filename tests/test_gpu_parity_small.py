@@ -63,6 +63,10 @@ def test_device_chunk_index_bit_exact(roast):
         rows[: N // 2] = rng.integers(0, 3_000_000, size=N // 2)
         tables = rng.integers(0, 26, size=N).astype(np.uint32)
         h = wl.draw_hash(rng)
+        if m == 60:      # tiny prime: fewer residues than chunks per row
+            h = dict(h, P=2, a0=1, a1=1, a2=1, a3=0, s0=1, s1=0, s2=1, s3=1)
+        if m == 1000:    # small prime: the per-chunk walk wraps around P several times
+            h = dict(h, P=7, a0=3, a1=5, a2=6, a3=2, s0=4, s1=1, s2=3, s3=6)
         d = roast.embed_desc(D, Z, m, 1.0, h)
         off, sgn = roast.roast_chunk_index_device(d, to_dev(rows), to_dev(tables))
         off, sgn = off.cpu().numpy(), sgn.cpu().numpy()
@@ -179,7 +183,8 @@ def test_zero_rows_is_a_noop(roast):
 
 # ------------------------------------------------------------------ lookup
 @pytest.mark.parametrize("D,Z,m,N", [(128, 32, 20000, 5000), (10, 4, 60, 333), (64, 64, 64, 100), (33, 1, 500, 77),
-                                     (96, 48, 1000, 1)])
+                                     (96, 48, 1000, 1), (128, 32, 300000, 40000), (96, 48, 9000, 30000),
+                                     (64, 8, 70000, 20000)])
 def test_lookup_matches_oracle(roast, D, Z, m, N):
     rng = np.random.default_rng(D + N)
     M = wl.draw_m(rng, m, ("normal", 0.02))
@@ -193,8 +198,13 @@ def test_lookup_matches_oracle(roast, D, Z, m, N):
     out = roast.roast_embed_fwd(d, to_dev(rows), to_dev(tables), to_dev(M))
     dM = torch.zeros(m, dtype=torch.float32, device="cuda")
     roast.roast_embed_bwd(d, to_dev(rows), to_dev(tables), to_dev(dOut), dM)
+    # with the workspace the library asks for, large batches take the bucketed path
+    ws = torch.empty(max(roast.roast_embed_bwd_workspace(d, N), 1), dtype=torch.uint8, device="cuda")
+    dM_ws = torch.zeros(m, dtype=torch.float32, device="cuda")
+    roast.roast_embed_bwd(d, to_dev(rows), to_dev(tables), to_dev(dOut), dM_ws, ws=ws)
     ref_out = oracle.embed_fwd(h, D, Z, float(lam), rows, tables, M)
     ref_dM = oracle.embed_bwd(h, D, Z, m, float(lam), rows, tables, dOut)
     # the forward is one fp32 multiply per element: exact up to one rounding
     assert rel_err(to_host_f64(out), ref_out) <= 1e-7
     assert rel_err(to_host_f64(dM), ref_dM) <= F32_TOL
+    assert rel_err(to_host_f64(dM_ws), ref_dM) <= F32_TOL
