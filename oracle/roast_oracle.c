@@ -217,17 +217,20 @@ int oracle_dm_window(const oracle_hash_t* h, uint32_t layer, int64_t I, int64_t 
   return err;
 }
 
-/* out[n, i] = lambda * g * M[h1(chunk) + (i mod Z)], chunk key = (table, row, i div Z). */
+/* out[n, i] = lambda * g * M[h1(chunk) + (i mod Z)], chunk key = (table, row, i div Z).
+ * The chunk's offset and sign are found once per chunk, then its elements are copied one by one. */
 int oracle_embed_fwd(const oracle_hash_t* h, int64_t D, int32_t Z, int64_t m_size, double lambda,
                      int64_t N, const int64_t* rows, const uint32_t* tables,
                      const float* M, double* out) {
-  for (int64_t n = 0; n < N; ++n)
-    for (int64_t i = 0; i < D; ++i) {
+  for (int64_t n = 0; n < N; ++n) {
+    if (rows[n] < 0) return 1;
+    for (int64_t c = 0; c * Z < D; ++c) {
       int64_t base; int32_t s;
-      if (rows[n] < 0) return 1;
-      if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)(i / Z), m_size, Z, &base, &s)) return 1;
-      out[n * D + i] = lambda * (double)s * (double)M[base + i % Z];
+      if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)c, m_size, Z, &base, &s)) return 1;
+      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i)
+        out[n * D + i] = lambda * (double)s * (double)M[base + i % Z];
     }
+  }
   return 0;
 }
 
@@ -235,12 +238,14 @@ int oracle_embed_fwd(const oracle_hash_t* h, int64_t D, int32_t Z, int64_t m_siz
 int oracle_embed_bwd(const oracle_hash_t* h, int64_t D, int32_t Z, int64_t m_size, double lambda,
                      int64_t N, const int64_t* rows, const uint32_t* tables,
                      const double* dOut, double* dM) {
-  for (int64_t n = 0; n < N; ++n)
-    for (int64_t i = 0; i < D; ++i) {
+  for (int64_t n = 0; n < N; ++n) {
+    if (rows[n] < 0) return 1;
+    for (int64_t c = 0; c * Z < D; ++c) {
       int64_t base; int32_t s;
-      if (rows[n] < 0) return 1;
-      if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)(i / Z), m_size, Z, &base, &s)) return 1;
-      dM[base + i % Z] += lambda * (double)s * dOut[n * D + i];
+      if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)c, m_size, Z, &base, &s)) return 1;
+      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i)
+        dM[base + i % Z] += lambda * (double)s * dOut[n * D + i];
     }
+  }
   return 0;
 }
