@@ -62,6 +62,7 @@ def main():
     d1 = roast.mm_desc(l1.H, l1.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l1.layer_id, mcfg.lam, mi.hash)
     d2 = roast.mm_desc(l2.H, l2.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l2.layer_id, mcfg.lam, mi.hash)
     M = to_dev(mi.M)
+    Mb = torch.empty(mcfg.m_size, dtype=torch.bfloat16, device="cuda")
     X = to_dev(mi.X[l1.name])
     dY = to_dev(mi.dY[l2.name])
     I = mcfg.I
@@ -70,6 +71,7 @@ def main():
     dH1 = torch.empty((I, l1.O), dtype=torch.bfloat16, device="cuda")
     dX = torch.empty((I, l1.H), dtype=torch.bfloat16, device="cuda")
     dM = torch.zeros(mcfg.m_size, dtype=torch.float32, device="cuda")
+    # workspace: required by the deterministic mode, optional (and used) in the atomic mode
     ws_bytes = max(roast.roast_mm_bwd_dM_workspace(d1, I, mode), roast.roast_mm_bwd_dM_workspace(d2, I, mode), 1)
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
 
@@ -85,7 +87,7 @@ def main():
 
     names = []
     if not args.embed_only:
-        names += ["mm_fwd_l1", "mm_fwd_l2", "mm_bwd_dx_l2", "mm_bwd_dM_l2", "mm_bwd_dx_l1", "mm_bwd_dM_l1"]
+        names += ["m_shadow", "mm_fwd_l1", "mm_fwd_l2", "mm_bwd_dx_l2", "mm_bwd_dM_l2", "mm_bwd_dx_l1", "mm_bwd_dM_l1"]
     if not args.mm_only:
         names += ["embed_fwd", "embed_bwd"]
 
@@ -100,11 +102,12 @@ def main():
 
         mark()
         if not args.embed_only:
-            roast.roast_mm_fwd(d1, X, M, H1); mark()
-            roast.roast_mm_fwd(d2, H1, M, Y); mark()
-            roast.roast_mm_bwd_dx(d2, dY, M, dH1); mark()
+            roast.roast_m_shadow_bf16(M, Mb); mark()       # once per step: M changes once per step
+            roast.roast_mm_fwd(d1, X, M, H1, M_bf16=Mb); mark()
+            roast.roast_mm_fwd(d2, H1, M, Y, M_bf16=Mb); mark()
+            roast.roast_mm_bwd_dx(d2, dY, M, dH1, M_bf16=Mb); mark()
             roast.roast_mm_bwd_dM(d2, H1, dY, dM, mode, ws); mark()
-            roast.roast_mm_bwd_dx(d1, dH1, M, dX); mark()
+            roast.roast_mm_bwd_dx(d1, dH1, M, dX, M_bf16=Mb); mark()
             roast.roast_mm_bwd_dM(d1, X, dH1, dM, mode, ws); mark()
         if not args.mm_only:
             roast.roast_embed_fwd(ed, rows, tables, eM, out); mark()
@@ -135,7 +138,7 @@ def main():
 
     flop_layer = {"l1": 2.0 * I * l1.H * l1.O, "l2": 2.0 * I * l2.H * l2.O}
     if not args.embed_only:
-        mm_ms = sum(v for k, v in per_call.items() if k.startswith("mm_"))
+        mm_ms = sum(v for k, v in per_call.items() if k.startswith("mm_") or k == "m_shadow")
         mm_flop = 3.0 * (flop_layer["l1"] + flop_layer["l2"])
         tflops = mm_flop / (mm_ms * 1e-3) / 1e12
         result["value"] = tflops

@@ -122,20 +122,33 @@ roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, cons
                                       const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream);
 
 /*
+ * bf16 copy of M (round to nearest even), |M|-sized -- never |W|-sized.  Optional: the bf16 kernels
+ * stage the weight operand in bfloat16 anyway (see the conventions above), so reading it from this
+ * copy gives bit-identical results with half the weight traffic.  Make it once per update of M and
+ * pass it to as many roast_mm_fwd / roast_mm_bwd_dx calls as share that M.
+ * shadow: DEVICE buffer of m_size 2-byte elements, owned by the caller.
+ */
+roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream);
+
+/*
  * ROAST-MM forward, Algorithm 1:  Y[I x O] = X[I x H] * W,  W recovered tile by tile from M.
  * X: I x H (ldx), Y: I x O (ldy), both of type `dt`; M: m_size fp32.  Y is overwritten.
+ * M_bf16: NULL, or the copy of this M made by roast_m_shadow_bf16 (used by the bf16 kernels only).
  */
-roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I,
-                          const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy, void* stream);
+roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                          const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream);
 
 /*
  * Gradient w.r.t. the input (Section 3.3):  dX[I x H] = dY[I x O] * W^T, W recovered from M.
- * dX is overwritten.
+ * dX is overwritten.  M_bf16 as for roast_mm_fwd.
  */
-roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I,
-                             const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx, void* stream);
+roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
+                             const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream);
 
-/* Bytes of workspace roast_mm_bwd_dM needs for these sizes and mode (0 = none needed). */
+/* Bytes of workspace roast_mm_bwd_dM can use for these sizes and mode (0 = none).
+ * DETERMINISTIC: required.  ATOMIC: optional -- with it (bf16 path, contraction split over several
+ * workgroups) the per-split products are summed in the workspace and scattered with one atomic per
+ * virtual weight; without it every split adds straight into dM. */
 size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode);
 
 /*
@@ -143,7 +156,7 @@ size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce
  *   dM[offset(x,y) + Z2*o1 + o2] += lambda * sign(x,y) * sum_i X[i, x*Z1+o1] * dY[i, y*Z2+o2]
  * for every element of every tile; colliding tiles add up.  dM: m_size fp32, accumulated into.
  * ws / ws_bytes: device scratch of at least roast_mm_bwd_dM_workspace() bytes (may be NULL / 0
- * when that is 0); its contents on return are unspecified.
+ * when that is 0 or, in ATOMIC mode, always); its contents on return are unspecified.
  */
 roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I,
                              const void* X, int64_t ldx, const void* dY, int64_t ldy,

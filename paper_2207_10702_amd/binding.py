@@ -17,7 +17,7 @@ ROAST_F32, ROAST_BF16 = 0, 1
 ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
-           "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
+           "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd"]
 
 
@@ -64,8 +64,9 @@ def load() -> C.CDLL:
     lib.roast_tile_index.argtypes = [MP, vp, vp]
     lib.roast_tile_index_device.argtypes = [MP, vp, vp, vp]
     lib.roast_chunk_index_device.argtypes = [EP, i64, vp, vp, vp, vp, vp]
-    lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, i64, vp]
-    lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, i64, vp]
+    lib.roast_m_shadow_bf16.argtypes = [vp, i64, vp, vp]
+    lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
+    lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.roast_mm_bwd_dM_workspace.argtypes = [MP, i64, i32]
     lib.roast_mm_bwd_dM_workspace.restype = sz
     lib.roast_mm_bwd_dM.argtypes = [MP, i32, i64, vp, i64, vp, i64, vp, i32, vp, sz, vp]
@@ -168,7 +169,28 @@ def roast_chunk_index_device(desc: RoastEmbedDesc, rows, table_ids, stream=None)
     return off, sgn
 
 
-def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None):
+def roast_m_shadow_bf16(M, shadow=None, stream=None):
+    """bf16 copy of M for the bf16 ROAST-MM kernels (make it once per update of M)."""
+    torch = _torch()
+    if shadow is None:
+        shadow = torch.empty(M.numel(), dtype=torch.bfloat16, device=M.device)
+    if shadow.numel() != M.numel():
+        raise ValueError("shadow must have as many elements as M")
+    _check(load().roast_m_shadow_bf16(_vec(M, torch.float32, "M"), M.numel(), _vec(shadow, torch.bfloat16, "shadow"),
+                                      _stream(stream)), "roast_m_shadow_bf16")
+    return shadow
+
+
+def _shadow_ptr(M, M_bf16) -> int:
+    if M_bf16 is None:
+        return 0
+    torch = _torch()
+    if M_bf16.numel() != M.numel():
+        raise ValueError("M_bf16 must have as many elements as M")
+    return _vec(M_bf16, torch.bfloat16, "M_bf16")
+
+
+def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None):
     torch = _torch()
     I = X.shape[0]
     if X.shape[1] != desc.H:
@@ -179,12 +201,12 @@ def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None):
         raise ValueError("Y must be I x O with X's dtype")
     xp, ldx = _mat(X, "X")
     yp, ldy = _mat(Y, "Y")
-    _check(load().roast_mm_fwd(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"), yp, ldy,
-                               _stream(stream)), "roast_mm_fwd")
+    _check(load().roast_mm_fwd(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"),
+                               _shadow_ptr(M, M_bf16), yp, ldy, _stream(stream)), "roast_mm_fwd")
     return Y
 
 
-def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None):
+def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None):
     torch = _torch()
     I = dY.shape[0]
     if dY.shape[1] != desc.O:
@@ -195,8 +217,8 @@ def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None):
         raise ValueError("dX must be I x H with dY's dtype")
     gp, ldy = _mat(dY, "dY")
     xp, ldx = _mat(dX, "dX")
-    _check(load().roast_mm_bwd_dx(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"), xp, ldx,
-                                  _stream(stream)), "roast_mm_bwd_dx")
+    _check(load().roast_mm_bwd_dx(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"),
+                                  _shadow_ptr(M, M_bf16), xp, ldx, _stream(stream)), "roast_mm_bwd_dx")
     return dX
 
 

@@ -98,8 +98,15 @@ roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, cons
   return chunk_index_launch(a, rows, table_ids, off_dev, sgn_dev, (hipStream_t)stream);
 }
 
+roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream) {
+  if (m_size < 0) return ROAST_ERR_ARG;
+  if (m_size == 0) return ROAST_OK;
+  if (!M || !shadow) return ROAST_ERR_ARG;
+  return shadow_bf16_launch(M, m_size, shadow, (hipStream_t)stream);
+}
+
 roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
-                          const float* M, void* Y, int64_t ldy, void* stream) {
+                          const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream) {
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -107,14 +114,14 @@ roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, con
   if (I == 0) return ROAST_OK;
   if (!X || !M || !Y || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
   if (dt == ROAST_BF16) {
-    st = mfma_mm_fwd(a, X, ldx, M, Y, ldy, (hipStream_t)stream);
+    st = mfma_mm_fwd(a, X, ldx, M, M_bf16, Y, ldy, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
   }
   return generic_mm_fwd(a, dt, X, ldx, M, Y, ldy, (hipStream_t)stream);
 }
 
 roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
-                             const float* M, void* dX, int64_t ldx, void* stream) {
+                             const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream) {
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -122,7 +129,7 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
   if (I == 0) return ROAST_OK;
   if (!dY || !M || !dX || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
   if (dt == ROAST_BF16) {
-    st = mfma_mm_bwd_dx(a, dY, ldy, M, dX, ldx, (hipStream_t)stream);
+    st = mfma_mm_bwd_dx(a, dY, ldy, M, M_bf16, dX, ldx, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
   }
   return generic_mm_bwd_dx(a, dt, dY, ldy, M, dX, ldx, (hipStream_t)stream);
@@ -131,8 +138,8 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
 size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode) {
   MMArgs a;
   if (make_mm_args(d, I, &a) != ROAST_OK) return 0;
-  if (mode != ROAST_REDUCE_DETERMINISTIC || I == 0) return 0;
-  return dm_det_workspace_bytes(a);
+  if (I == 0) return 0;
+  return mode == ROAST_REDUCE_DETERMINISTIC ? dm_det_workspace_bytes(a) : dm_ws_workspace_bytes(a);
 }
 
 roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
@@ -151,6 +158,12 @@ roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
     return dm_det_run(a, dt, X, ldx, dY, ldy, dM, ws, (hipStream_t)stream);
   }
   if (dt == ROAST_BF16) {
+    // optional workspace: per-split products are summed before they are scattered (fewer atomics)
+    const size_t want = dm_ws_workspace_bytes(a);
+    if (want && ws && ws_bytes >= want) {
+      st = dm_ws_run(a, X, ldx, dY, ldy, dM, ws, (hipStream_t)stream);
+      if (st != ROAST_ERR_UNSUPPORTED) return st;
+    }
     st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, dM, nullptr, 0, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
   }

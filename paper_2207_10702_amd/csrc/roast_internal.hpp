@@ -57,6 +57,11 @@ roast_status generic_mm_bwd_dM_atomic(const MMArgs& a, roast_dtype dt, const voi
 roast_status generic_dm_launch(const MMArgs& a, roast_dtype dt, const void* X, int64_t ldx, const void* dY,
                                int64_t ldy, float* dM, float* Gws, int splits, hipStream_t s);
 
+// ---- ATOMIC mode with a workspace: per-split products to ws, then one scatter (roast_reduce.hip)
+size_t dm_ws_workspace_bytes(const MMArgs& a);           // 0: not applicable (direct atomics are used)
+roast_status dm_ws_run(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM, void* ws,
+                       hipStream_t s);
+
 // ---- deterministic dM reduction (roast_reduce.hip)
 // Workspace layout: [G: S*H*O floats][tile keys: nT uint64][sorted tile ids: nT uint32]
 int dm_det_splits(const MMArgs& a);                       // S: how many partial products of G are kept
@@ -66,10 +71,12 @@ roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t 
 
 // ---- bf16 MFMA kernels (roast_mm_mfma.hip): return ROAST_ERR_UNSUPPORTED when the shape does not
 // meet their divisibility rules; the caller then falls back to the generic kernels.
-roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy,
-                         hipStream_t s);
-roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx,
-                            hipStream_t s);
+// M_bf16 (optional): bf16 copy of M made by shadow_bf16_launch; halves the weight traffic.
+roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s);
+roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
+                         int64_t ldy, hipStream_t s);
+roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
+                            void* dX, int64_t ldx, hipStream_t s);
 // Gws == nullptr: atomically add lambda*sign*G into dM.  Gws != nullptr: store raw per-split G there
 // ([splits][H][O] floats) for the deterministic reduction; `splits` must equal dm_det_splits().
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,

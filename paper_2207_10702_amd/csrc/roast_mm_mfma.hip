@@ -39,6 +39,13 @@ struct __attribute__((packed, aligned(4))) f4u {  // 4 floats, 4-byte aligned (t
   float v[4];
 };
 
+struct __attribute__((packed, aligned(2))) h4u {  // 4 bf16, 2-byte aligned (tile bases in the bf16 shadow of M)
+  uint16_t v[4];
+};
+struct __attribute__((packed, aligned(2))) h8u {
+  uint16_t v[8];
+};
+
 constexpr int BK = 64;
 constexpr int kMaxTable = 512;  // tile-table entries a workgroup may need
 enum { MODE_FWD = 0, MODE_DX = 1, MODE_DM = 2 };
@@ -66,12 +73,31 @@ struct KernArgs {
   const uint16_t* B;   // DM: dY
   int64_t ldb;
   const float* M;      // FWD / DX
+  const uint16_t* Mb;  // FWD / DX: bf16 copy of M (SHADOW kernels)
   uint16_t* C;         // FWD: Y, DX: dX
   int64_t ldc;
   float* dM;           // DM, atomic mode
   float* G;            // DM, deterministic mode: raw products [split][H][O]
   int rows_per_split;  // DM
+  int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
 };
+
+// Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Blocks that share
+// an operand slab (same row block -> same rows of X / dY) should therefore run on the same XCD:
+// XCD j takes the j-th contiguous eighth of the row-major block order (z, y, x), so that an operand
+// slab is fetched into one L2 and reused there by all the column blocks, instead of being fetched by
+// eight L2s from the memory-side cache.  Returns false for the padding workgroups of the last eighth.
+__device__ inline bool block_coords(const KernArgs& p, int* bx, int* by, int* bz) {
+  const int total = p.nbx * p.nby * p.nbz;
+  const int chunk = (total + 7) / 8;
+  const int w = blockIdx.x;
+  const int t = (w & 7) * chunk + (w >> 3);
+  if ((w >> 3) >= chunk || t >= total) return false;
+  *bx = t % p.nbx;
+  *by = (t / p.nbx) % p.nby;
+  *bz = t / (p.nbx * p.nby);
+  return true;
+}
 
 // Transposing loader for a bf16 [BK rows (k)][W cols] tile whose rows are contiguous in memory:
 // each thread owns an 8(k) x CW(cols) block (CW = W/32), loads its 8 row pieces, and writes CW
@@ -134,45 +160,69 @@ struct ProdCtx {
   int ta_col, tb_col;
 };
 
-template <int MODE, int BM, int BN>
+template <int MODE, int BM, int BN, bool SHADOW>
 struct RegSet {
   using Ctx = ProdCtx<MODE, BM, BN>;
   uint4v a_reg[MODE == MODE_DM ? 1 : Ctx::A_LOADS];
-  floatx4 fw_reg[MODE == MODE_FWD ? Ctx::FW_BLK * 8 : 1];
+  // weight tile from fp32 M ...
+  floatx4 fw_reg[(MODE == MODE_FWD && !SHADOW) ? Ctx::FW_BLK * 8 : 1];
   float fw_sgn;
-  floatx4 dx_reg[MODE == MODE_DX ? Ctx::DX_LOADS * 2 : 1];
+  floatx4 dx_reg[(MODE == MODE_DX && !SHADOW) ? Ctx::DX_LOADS * 2 : 1];
   float dx_sgn[MODE == MODE_DX ? Ctx::DX_LOADS : 1];
+  // ... or from its bf16 shadow
+  uint2v fs_reg[(MODE == MODE_FWD && SHADOW) ? Ctx::FW_BLK * 8 : 1];
+  uint4v ds_reg[(MODE == MODE_DX && SHADOW) ? Ctx::DX_LOADS : 1];
   TLoad<MODE == MODE_DM ? BM : 128> ta;
   TLoad<MODE == MODE_DM ? BN : 128> tb;
 };
 
-template <int MODE, int BM, int BN, int WGM, int WGN>
+#ifdef ROAST_EXP_TRACE
+#define TRACE(slot) do { if (trace_on && lane == 0 && (slot) < 64) trace_buf[wave * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
+#else
+#define TRACE(slot) do {} while (0)
+#endif
+
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
 __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
   static_assert(WGM * WGN == 4, "4 consumer waves");
   using Ctx = ProdCtx<MODE, BM, BN>;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // consumer wave tile
   constexpr int MI = WTM / 32, NI = WTN / 32;    // 32x32 blocks per wave
-  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE = A_BYTES + B_BYTES;
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
   constexpr int EPI_STRIDE = WTN * 2 + 16;       // bytes per row of a wave's epilogue buffer
   constexpr int EPI_BYTES = 4 * 32 * EPI_STRIDE;
+  constexpr int NA = 2;                          // LDS stages per operand
+  constexpr int TILES_BYTES = NA * A_BYTES + 2 * B_BYTES;
 
-  extern __shared__ __attribute__((aligned(128))) char smem[];
-  int64_t* s_off = reinterpret_cast<int64_t*>(smem + 2 * STAGE + EPI_BYTES);
-  float* s_sgn = reinterpret_cast<float*>(smem + 2 * STAGE + EPI_BYTES + kMaxTable * 8);
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int64_t* s_off = reinterpret_cast<int64_t*>(smem + TILES_BYTES + EPI_BYTES);
+  float* s_sgn = reinterpret_cast<float*>(smem + TILES_BYTES + EPI_BYTES + kMaxTable * 8);
+  auto a_stage = [&](int step) -> char* { return smem + (step % NA) * A_BYTES; };
+  auto b_stage = [&](int step) -> char* { return smem + NA * A_BYTES + (step & 1) * B_BYTES; };
 
   const MMArgs& a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const bool producer = wave >= 4;
   const int I = (int)a.I;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int bx, by, bz;
+  if (!block_coords(p, &bx, &by, &bz)) return;   // whole workgroup leaves before any barrier
+  const int m0 = by * BM, n0 = bx * BN;
+#ifdef ROAST_EXP_TRACE
+  const bool trace_on = (blockIdx.x == 300) && p.dM != nullptr && MODE != MODE_DM;
+  unsigned long long* trace_buf = reinterpret_cast<unsigned long long*>(p.dM);
+#endif
   const int Mdim = MODE == MODE_DM ? (int)a.H : I;
   const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
   if (MODE == MODE_DM) {
-    k_begin = blockIdx.z * p.rows_per_split;
+    k_begin = bz * p.rows_per_split;
     k_end = min(I, k_begin + p.rows_per_split);
   }
+#ifdef ROAST_EXP_NOLOOP
+  const int nsteps = 0;
+#else
   const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
+#endif
 
   // ---- tile table (all 512 threads)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
@@ -199,8 +249,12 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
       else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
       else { x = x0 + e / TN; y = y0 + e % TN; }
+#ifdef ROAST_EXP_NOTABLE
+      s_off[e] = (int64_t)(x + y); s_sgn[e] = 1.f;
+#else
       s_off[e] = block_offset(a.hash, a.layer, x, y);
       s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
+#endif
     }
   }
   __syncthreads();
@@ -209,6 +263,10 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
     // =========================================================================== producer waves
     // Loads are unconditional: rows / columns outside the problem are redirected to a valid address
     // and their products are never stored; only the contraction tail of the dM product is zeroed.
+    // The producers' instructions are few but on the critical path of every step; with equal
+    // priority the SIMD's arbiter favours the consumer wave and the producer only runs while the
+    // consumer sits at the barrier (measured: the two phases then serialise).
+    __builtin_amdgcn_s_setprio(3);
     Ctx c;
     c.ptid = tid - 256;
     const int pt = c.ptid;
@@ -235,7 +293,7 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       c.tb_col = min(n0 + (pt & 31) * (BN / 32), (int)a.O - BN / 32);
     }
 
-    auto load_global = [&](RegSet<MODE, BM, BN>& r, int step) {
+    auto load_global = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
       const int k0 = k_begin + step * BK;
 #ifdef ROAST_EXP_NOLOAD
       if (step > 1) return;
@@ -250,15 +308,32 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       __builtin_amdgcn_sched_barrier(0);
       if (MODE == MODE_FWD) {
         const int e = (k0 / a.Z1) * TN + c.fw_yl;
-        const float* base = p.M + s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (pt / Ctx::FW_NG)) + c.fw_nin;
+        const int64_t rel = s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (pt / Ctx::FW_NG)) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
 #pragma unroll
         for (int b = 0; b < Ctx::FW_BLK; ++b)
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
-            const f4u m = *reinterpret_cast<const f4u*>(base + (int64_t)(8 * Ctx::FW_KBS * b + q) * a.Z2);
-            r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
+            const int64_t at = rel + (int64_t)(8 * Ctx::FW_KBS * b + q) * a.Z2;
+            if constexpr (SHADOW) {
+              const h4u m = *reinterpret_cast<const h4u*>(p.Mb + at);
+              r.fs_reg[b * 8 + q] = uint2v{(uint32_t)m.v[0] | ((uint32_t)m.v[1] << 16),
+                                           (uint32_t)m.v[2] | ((uint32_t)m.v[3] << 16)};
+            } else {
+              const f4u m = *reinterpret_cast<const f4u*>(p.M + at);
+              r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
+            }
           }
+      } else if (MODE == MODE_DX && SHADOW) {
+        const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
+#pragma unroll
+        for (int q = 0; q < Ctx::DX_LOADS; ++q) {
+          const int e = kt + c.dx_ent[q];
+          const h8u m = *reinterpret_cast<const h8u*>(p.Mb + s_off[e] + c.dx_rowoff[q] + kin);
+          r.ds_reg[q] = uint4v{(uint32_t)m.v[0] | ((uint32_t)m.v[1] << 16), (uint32_t)m.v[2] | ((uint32_t)m.v[3] << 16),
+                               (uint32_t)m.v[4] | ((uint32_t)m.v[5] << 16), (uint32_t)m.v[6] | ((uint32_t)m.v[7] << 16)};
+          r.dx_sgn[q] = s_sgn[e];
+        }
       } else if (MODE == MODE_DX) {
         const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
 #pragma unroll
@@ -279,19 +354,33 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       __builtin_amdgcn_sched_barrier(0);
     };
 
-    auto store_lds = [&](RegSet<MODE, BM, BN>& r, int step) {
+    auto store_lds = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
       const int k0 = k_begin + step * BK;
 #ifdef ROAST_EXP_NOLDSW
       if (step > 1) return;
 #endif
-      char* At = smem + (step & 1) * STAGE;
-      char* Bt = At + A_BYTES;
+      char* At = a_stage(step);
+      char* Bt = b_stage(step);
       if (MODE != MODE_DM) {
 #pragma unroll
         for (int q = 0; q < Ctx::A_LOADS; ++q)
           *reinterpret_cast<uint4v*>(At + lds_off((pt >> 3) + 32 * q, pt & 7)) = r.a_reg[q];
       }
-      if (MODE == MODE_FWD) {
+      if (MODE == MODE_FWD && SHADOW) {
+        // flipping the sign bit of a bf16 equals rounding the negated fp32 value
+        const uint32_t flip = r.fw_sgn < 0.f ? 0x80008000u : 0u;
+#pragma unroll
+        for (int b = 0; b < Ctx::FW_BLK; ++b)
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) {
+            const uint32_t sel = (cc & 1) ? 0x07060302u : 0x05040100u;
+            uint4v o;
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr)
+              o[pr] = __builtin_amdgcn_perm(r.fs_reg[b * 8 + 2 * pr + 1][cc >> 1], r.fs_reg[b * 8 + 2 * pr][cc >> 1], sel) ^ flip;
+            *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (pt % Ctx::FW_NG) + cc, pt / Ctx::FW_NG + Ctx::FW_KBS * b)) = o;
+          }
+      } else if (MODE == MODE_FWD) {
         const float sg = r.fw_sgn;
 #pragma unroll
         for (int b = 0; b < Ctx::FW_BLK; ++b)
@@ -303,6 +392,13 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
               o[pr] = pack_bf16x2(r.fw_reg[b * 8 + 2 * pr][cc] * sg, r.fw_reg[b * 8 + 2 * pr + 1][cc] * sg);
             *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (pt % Ctx::FW_NG) + cc, pt / Ctx::FW_NG + Ctx::FW_KBS * b)) = o;
           }
+      } else if (MODE == MODE_DX && SHADOW) {
+#pragma unroll
+        for (int q = 0; q < Ctx::DX_LOADS; ++q) {
+          const uint32_t flip = r.dx_sgn[q] < 0.f ? 0x80008000u : 0u;
+          const uint4v v = r.ds_reg[q];
+          *reinterpret_cast<uint4v*>(Bt + lds_off((pt >> 3) + 32 * q, pt & 7)) = uint4v{v[0] ^ flip, v[1] ^ flip, v[2] ^ flip, v[3] ^ flip};
+        }
       } else if (MODE == MODE_DX) {
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
@@ -320,27 +416,35 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
 
     // Barrier s publishes stage (s & 1) holding step s.  Filling stage (s & 1) for step s is safe
     // once barrier s-1 has been passed: the consumers finished reading it (step s-2) before that.
-    // Loads run two steps ahead of their use; the loop body is branch-free (a step index past the
-    // end is clamped and its data never stored) so that the wait for set r0 can leave r1's newer
-    // loads in flight.
-    RegSet<MODE, BM, BN> r0, r1;
+    // Loads run NSETS steps ahead of their use (one register set per step in flight): with a step
+    // of ~0.5 us and a loaded memory latency of 1-2 us, two sets leave the producers latency-bound.
+    // The loop body is branch-free (a step index past the end is clamped and its data never
+    // stored) so that the wait for the oldest set can leave the newer loads in flight.
+    constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : 4;   // fp32 weight tiles take twice the registers
+    RegSet<MODE, BM, BN, SHADOW> rs[NSETS];
     const int last = nsteps - 1;
     if (nsteps > 0) {
-      load_global(r0, 0);
-      load_global(r1, min(1, last));
+#pragma unroll
+      for (int j = 0; j < NSETS; ++j) load_global(rs[j], min(j, last));
     }
     int s = 0;
-    for (; s + 1 < nsteps; s += 2) {
-      store_lds(r0, s);
-      load_global(r0, min(s + 2, last));
-      __syncthreads();                                   // barrier s
-      store_lds(r1, s + 1);
-      load_global(r1, min(s + 3, last));
-      __syncthreads();                                   // barrier s + 1
+    for (; s + NSETS <= nsteps; s += NSETS) {
+#pragma unroll
+      for (int j = 0; j < NSETS; ++j) {
+        TRACE(3 * (s + j) + 0);
+        store_lds(rs[j], s + j);
+        TRACE(3 * (s + j) + 1);
+        load_global(rs[j], min(s + j + NSETS, last));
+        TRACE(3 * (s + j) + 2);
+        __syncthreads();                                 // barrier s + j
+      }
     }
-    if (s < nsteps) {                                    // odd number of steps
-      store_lds(r0, s);
-      __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NSETS - 1; ++j) {                // remaining steps (fewer than NSETS)
+      if (s + j < nsteps) {
+        store_lds(rs[j], s + j);
+        __syncthreads();
+      }
     }
     return;
   }
@@ -359,9 +463,11 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
   // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
   // Fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued.
   for (int s = 0; s < nsteps; ++s) {
-    __syncthreads();                                     // barrier s: stage (s & 1) holds step s
-    const char* At = smem + (s & 1) * STAGE;
-    const char* Bt = At + A_BYTES;
+    TRACE(3 * s + 0);
+    __syncthreads();                                     // barrier s: stages hold step s
+    TRACE(3 * s + 1);
+    const char* At = a_stage(s);
+    const char* Bt = b_stage(s);
     bf16x8 af[2][MI], bfr[2][NI];
     auto fetch = [&](int ks, int buf) {
 #pragma unroll
@@ -388,14 +494,14 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
         }
       __builtin_amdgcn_sched_barrier(0);
     }
+    TRACE(3 * s + 2);
   }
-
   // ---- epilogue (consumer waves only; the producers have left)
   if (MODE != MODE_DM) {
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
     // Each wave stages one 32-row block at a time in its own LDS buffer and writes it out 16 bytes
     // per lane, row-contiguous.
-    char* ebuf = smem + 2 * STAGE + wave * (32 * EPI_STRIDE);
+    char* ebuf = smem + TILES_BYTES + wave * (32 * EPI_STRIDE);
     constexpr int CPR = WTN / 8;              // 16-byte chunks per row of the wave tile
     constexpr int RPI = 64 / CPR;             // rows per store instruction
 #pragma unroll
@@ -431,7 +537,7 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
         const int ob = n0 + wn * WTN + j * 32;
         if (hb >= (int)a.H || ob >= (int)a.O) continue;
         if (p.G) {
-          float* g = p.G + ((int64_t)blockIdx.z * a.H + hb) * a.O + ob + lc;
+          float* g = p.G + ((int64_t)bz * a.H + hb) * a.O + ob + lc;
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int r = 8 * (e >> 2) + lr + (e & 3);
@@ -454,22 +560,33 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
   }
 }
 
-template <int BM, int BN, int WGN>
-constexpr int smem_bytes() { return 2 * (BM + BN) * 128 + 4 * 32 * ((BN / WGN) * 2 + 16) + kMaxTable * 12; }
+template <int MODE, int BM, int BN, int WGN>
+constexpr int smem_bytes() {
+  return (2 * BM + 2 * BN) * 128 + 4 * 32 * ((BN / WGN) * 2 + 16) + kMaxTable * 12;
+}
 
-template <int MODE, int BM, int BN, int WGM, int WGN>
-roast_status launch(const KernArgs& p, dim3 grid, hipStream_t s) {
-  constexpr int smem = smem_bytes<BM, BN, WGN>();
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
+roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
+  const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
+  if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
+  p.nbx = (int)blocks.x; p.nby = (int)blocks.y; p.nbz = (int)blocks.z;
+  const dim3 grid((unsigned)((total + 7) / 8 * 8));
+  constexpr int smem = smem_bytes<MODE, BM, BN, WGN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool configured = false;   // one attribute call per instantiation per process
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN>), grid, dim3(512), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3(512), smem, s, p);
   return hip_status(hipGetLastError());
+}
+
+__global__ __launch_bounds__(256) void k_shadow_bf16(const float* __restrict__ M, int64_t n, uint16_t* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = __builtin_bit_cast(uint16_t, (__bf16)M[i]);
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -477,32 +594,47 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 }  // namespace
 
-roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, void* Y, int64_t ldy,
-                         hipStream_t s) {
+#ifdef ROAST_EXP_TRACE
+void* g_roast_trace = nullptr;
+extern "C" void roast_set_trace(void* p) { g_roast_trace = p; }
+#endif
+
+roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s) {
+  const int64_t blocks = (m_size + 255) / 256;
+  if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_shadow_bf16, dim3((unsigned)blocks), dim3(256), 0, s, M, m_size, (uint16_t*)shadow);
+  return hip_status(hipGetLastError());
+}
+
+roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
+                         int64_t ldy, hipStream_t s) {
   if (a.Z1 % BK != 0 || a.H % a.Z1 != 0 || a.Z2 % 4 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
       !aligned16(X) || !aligned16(Y))
     return ROAST_ERR_UNSUPPORTED;
   constexpr int BM = 256, BN = 128;
   if (a.nTx * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
-  p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.C = (uint16_t*)Y; p.ldc = ldy;
+  p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)Y; p.ldc = ldy;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
-  if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_FWD, BM, BN, 2, 2>(p, grid, s);
+#ifdef ROAST_EXP_TRACE
+  { extern void* g_roast_trace; p.dM = (float*)g_roast_trace; }
+#endif
+  if (M_bf16) return launch<MODE_FWD, BM, BN, 2, 2, true>(p, grid, s);
+  return launch<MODE_FWD, BM, BN, 2, 2, false>(p, grid, s);
 }
 
-roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, void* dX, int64_t ldx,
-                            hipStream_t s) {
+roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
+                            void* dX, int64_t ldx, hipStream_t s) {
   if (a.Z2 % BK != 0 || a.O % a.Z2 != 0 || a.H % 8 != 0 || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) ||
       !aligned16(dX))
     return ROAST_ERR_UNSUPPORTED;
   constexpr int BM = 256, BN = 128;
   if (a.nTy * (cdiv(BN, a.Z1) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
-  p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.C = (uint16_t*)dX; p.ldc = ldx;
+  p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)dX; p.ldc = ldx;
   const dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
-  if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_DX, BM, BN, 2, 2>(p, grid, s);
+  if (M_bf16) return launch<MODE_DX, BM, BN, 2, 2, true>(p, grid, s);
+  return launch<MODE_DX, BM, BN, 2, 2, false>(p, grid, s);
 }
 
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
@@ -528,8 +660,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.B = (const uint16_t*)dY; p.ldb = ldy; p.dM = dM; p.G = Gws;
   p.rows_per_split = (int)rows;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
-  if (grid.y > 65535) return ROAST_ERR_UNSUPPORTED;
-  return launch<MODE_DM, BM, BN, 2, 2>(p, grid, s);
+  return launch<MODE_DM, BM, BN, 2, 2, false>(p, grid, s);
 }
 
 }  // namespace roast

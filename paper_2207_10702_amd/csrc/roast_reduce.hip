@@ -88,7 +88,75 @@ __global__ __launch_bounds__(256) void k_dm_gather(MMArgs a, int splits, const f
   if (any) dM[j] += total;
 }
 
+// Sum the per-split products and scatter them: one workgroup per (tile, block of rows of the tile).
+// dM[offset + Z2*o1 + o2] += lambda * sign * sum_s G[s][x*Z1 + o1][y*Z2 + o2].
+// One atomic per virtual weight instead of one per weight and split.  Needs Z2 % 4 == 0, O % 4 == 0.
+__global__ __launch_bounds__(256) void k_dm_scatter(MMArgs a, int splits, int rows_per_wg,
+                                                    const float* __restrict__ G, float* __restrict__ dM) {
+  __shared__ int64_t s_off;
+  __shared__ float s_scale;
+  const int chunks = (a.Z1 + rows_per_wg - 1) / rows_per_wg;
+  const int64_t tile = blockIdx.x / chunks;
+  const int r_begin = (blockIdx.x % chunks) * rows_per_wg;
+  const int x = (int)(tile / a.nTy), y = (int)(tile % a.nTy);
+  if (threadIdx.x == 0) {
+    s_off = block_offset(a.hash, a.layer, (uint64_t)x, (uint64_t)y);
+    s_scale = a.lambda * (float)block_sign(a.hash, a.layer, (uint64_t)x, (uint64_t)y);
+  }
+  __syncthreads();
+  const int64_t off = s_off;
+  const float scale = s_scale;
+  const int q4 = a.Z2 / 4;                                  // float4 groups per tile row
+  const int n4 = min(rows_per_wg, a.Z1 - r_begin) * q4;
+  const int64_t plane = a.H * a.O;
+  typedef float vf4 __attribute__((ext_vector_type(4)));
+  for (int e = threadIdx.x; e < n4; e += 256) {
+    const int r = r_begin + e / q4, c = (e % q4) * 4;
+    const int64_t h = (int64_t)x * a.Z1 + r, o = (int64_t)y * a.Z2 + c;
+    if (h >= a.H || o >= a.O) continue;
+    const float* g = G + h * a.O + o;
+    vf4 acc = *reinterpret_cast<const vf4*>(g);
+    for (int s = 1; s < splits; ++s) acc += *reinterpret_cast<const vf4*>(g + (int64_t)s * plane);
+    float* d = dM + off + (int64_t)a.Z2 * r + c;
+    unsafeAtomicAdd(d + 0, scale * acc.x);
+    unsafeAtomicAdd(d + 1, scale * acc.y);
+    unsafeAtomicAdd(d + 2, scale * acc.z);
+    unsafeAtomicAdd(d + 3, scale * acc.w);
+  }
+}
+
 }  // namespace
+
+// ---- split products through the workspace, then one scatter (the fast path of the ATOMIC mode when
+// the caller provides a workspace): S*H*O floats.
+int dm_ws_splits(const MMArgs& a) {
+  if (a.Z2 % 4 != 0 || a.O % 4 != 0) return 0;
+  const int64_t tiles = ((a.H + 255) / 256) * ((a.O + 127) / 128);
+  int64_t s = (512 + tiles - 1) / tiles;
+  const int64_t cap = (a.I + 255) / 256;
+  if (s > cap) s = cap;
+  return s > 1 ? (int)s : 0;          // a single split gains nothing over direct atomics
+}
+
+size_t dm_ws_workspace_bytes(const MMArgs& a) {
+  const int s = dm_ws_splits(a);
+  return s ? (size_t)s * (size_t)a.H * (size_t)a.O * sizeof(float) : 0;
+}
+
+roast_status dm_ws_run(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM, void* ws,
+                       hipStream_t s) {
+  const int splits = dm_ws_splits(a);
+  if (!splits) return ROAST_ERR_UNSUPPORTED;
+  float* G = (float*)ws;
+  roast_status st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, nullptr, G, splits, s);
+  if (st != ROAST_OK) return st;      // UNSUPPORTED: the caller falls back to direct atomics
+  const int rows_per_wg = a.Z2 >= 1024 ? 1 : (int)((4096 / a.Z2) > 0 ? (4096 / a.Z2) : 1);
+  const int chunks = (a.Z1 + rows_per_wg - 1) / rows_per_wg;
+  const int64_t blocks = a.nTx * a.nTy * chunks;
+  if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_dm_scatter, dim3((unsigned)blocks), dim3(256), 0, s, a, splits, rows_per_wg, G, dM);
+  return hip_status(hipGetLastError());
+}
 
 int dm_det_splits(const MMArgs& a) {
   // A fixed function of the shape only, so that the summation order never depends on the machine.

@@ -103,8 +103,20 @@ def run_mm(roast, dtype, seed, I, H, O, Z1, Z2, m, lam=1.0, use_sign=True, align
         Xd, dYd, Y, dX = to_dev(X), to_dev(dY), None, None
     Y = roast.roast_mm_fwd(d, Xd, Md, Y)
     dX = roast.roast_mm_bwd_dx(d, dYd, Md, dX)
+    if dtype == "bf16":
+        # reading the weights from the bf16 copy of M must not change a single bit
+        Mb = roast.roast_m_shadow_bf16(Md)
+        assert torch.equal(Mb, Md.to(torch.bfloat16))
+        Y2 = roast.roast_mm_fwd(d, Xd, Md, M_bf16=Mb)
+        dX2 = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=Mb)
+        assert torch.equal(Y2, Y.contiguous()) and torch.equal(dX2, dX.contiguous())
     dM = torch.zeros(m, dtype=torch.float32, device="cuda")
     roast.roast_mm_bwd_dM(d, Xd, dYd, dM)
+    # ATOMIC mode with the optional workspace (per-split products summed before the scatter)
+    wsa = torch.empty(max(roast.roast_mm_bwd_dM_workspace(d, I, roast.ROAST_REDUCE_ATOMIC), 1),
+                      dtype=torch.uint8, device="cuda")
+    dM_wsa = torch.zeros(m, dtype=torch.float32, device="cuda")
+    roast.roast_mm_bwd_dM(d, Xd, dYd, dM_wsa, roast.ROAST_REDUCE_ATOMIC, wsa)
     ws = torch.empty(max(roast.roast_mm_bwd_dM_workspace(d, I, roast.ROAST_REDUCE_DETERMINISTIC), 1),
                      dtype=torch.uint8, device="cuda")
     dM_det = torch.zeros(m, dtype=torch.float32, device="cuda")
@@ -117,7 +129,8 @@ def run_mm(roast, dtype, seed, I, H, O, Z1, Z2, m, lam=1.0, use_sign=True, align
     W = oracle.materialize_w(h, 5, H, O, Z1, Z2, float(lam), M)
     ref = dict(Y=oracle.mm_fwd(Xo, W), dX=oracle.mm_bwd_dx(dYo, W),
                dM=oracle.mm_bwd_dm(h, 5, Z1, Z2, m, float(lam), Xo, dYo))
-    got = dict(Y=to_host_f64(Y), dX=to_host_f64(dX), dM=to_host_f64(dM), dM_det=to_host_f64(dM_det))
+    got = dict(Y=to_host_f64(Y), dX=to_host_f64(dX), dM=to_host_f64(dM), dM_det=to_host_f64(dM_det),
+               dM_wsa=to_host_f64(dM_wsa))
     assert torch.equal(dM_det, dM_det2), "deterministic mode must be bit-reproducible"
     return got, ref
 
@@ -133,6 +146,7 @@ def test_mm_fp32_matches_oracle(roast, shape):
 # shapes that meet the MFMA kernels' divisibility rules (several 256x256 workgroup tiles, ragged I and
 # ragged O / H against the workgroup tile, 64- and 128-wide hash tiles, |M| == tile)
 MFMA_SHAPES = [
+    (2100, 256, 128, 64, 64, 30000),    # long contraction: several I-splits, workspace scatter path
     (300, 128, 320, 64, 64, 20000),
     (513, 256, 128, 128, 128, 40000),
     (256, 192, 96, 64, 32, 9000),
@@ -147,6 +161,7 @@ def test_mm_bf16_matches_oracle(roast, shape):
     for k in ("Y", "dX", "dM"):
         assert rel_err(got[k], ref[k]) <= BF16_TOL, k
     assert rel_err(got["dM_det"], ref["dM"]) <= BF16_TOL
+    assert rel_err(got["dM_wsa"], ref["dM"]) <= BF16_TOL
 
 
 @pytest.mark.parametrize("dtype,tol", [("f32", F32_TOL), ("bf16", BF16_TOL)])

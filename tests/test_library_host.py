@@ -69,10 +69,11 @@ def test_argument_validation_returns_status_codes_without_touching_the_gpu():
     bad_hash = binding.mm_desc(64, 64, 8, 8, 1000, 0, 1.0, dict(h, a1=h["P"]))
     assert lib.roast_tile_index(C.byref(bad_hash), None, None) == 3
     # null tensors are refused before any launch
-    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, None, 64, None, None, 64, None) == 1
-    assert lib.roast_mm_fwd(C.byref(ok), 7, 4, 1, 64, 1, 1, 64, None) == 1          # bad dtype enum
-    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, 1, 63, 1, 1, 64, None) == 1          # ldx < H
-    assert lib.roast_mm_fwd(C.byref(ok), 0, 0, None, 64, None, None, 64, None) == 0  # I == 0: no-op
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, None, 64, None, None, None, 64, None) == 1
+    assert lib.roast_mm_fwd(C.byref(ok), 7, 4, 1, 64, 1, None, 1, 64, None) == 1          # bad dtype enum
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 4, 1, 63, 1, None, 1, 64, None) == 1          # ldx < H
+    assert lib.roast_mm_fwd(C.byref(ok), 0, 0, None, 64, None, None, None, 64, None) == 0  # I == 0: no-op
+    assert lib.roast_m_shadow_bf16(None, 5, None, None) == 1
     assert lib.roast_mm_bwd_dM(C.byref(ok), 0, 4, 1, 64, 1, 64, 1, 1, None, 0, None) == 4  # no workspace
     e = binding.embed_desc(16, 4, 3, 1.0, h)
     assert lib.roast_embed_fwd(C.byref(e), 5, 1, 1, 1, 1, None) == 3
