@@ -58,6 +58,21 @@ roast_status generic_dm_launch(const MMArgs& a, roast_dtype dt, const void* X, i
                                int64_t ldy, float* dM, float* Gws, int splits, hipStream_t s);
 
 // ---- ATOMIC mode with a workspace: per-split products to ws, then one scatter (roast_reduce.hip)
+// Number of parts the contraction (over the I rows) of the dM product is cut into when the output
+// has `tiles` workgroup tiles.  The 256 CUs hold one workgroup each, so a launch runs in
+// ceil(tiles*s/256) rounds of ceil(steps/s) 64-row steps plus a fixed cost of about 8 steps per
+// workgroup; the s with the least rounds*(steps + 8) wins, ties go to fewer parts.  A function of
+// the shape only, so results do not depend on the machine's state.
+inline int dm_pick_splits(int64_t tiles, int64_t I) {
+  const int64_t steps = (I + 63) / 64;
+  int best = 1;
+  int64_t best_cost = INT64_MAX;
+  for (int s = 1; s <= 16 && (s == 1 || steps / s >= 4); ++s) {
+    const int64_t cost = ((tiles * s + 255) / 256) * ((steps + s - 1) / s + 8);
+    if (cost < best_cost) { best_cost = cost; best = s; }
+  }
+  return best;
+}
 size_t dm_ws_workspace_bytes(const MMArgs& a);           // 0: not applicable (direct atomics are used)
 roast_status dm_ws_run(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM, void* ws,
                        hipStream_t s);

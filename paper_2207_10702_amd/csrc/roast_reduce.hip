@@ -8,6 +8,7 @@
 // [offset, offset + Z1*Z2) covers j -- a contiguous run of the ranked table because all tiles have
 // the same length -- and adds their contributions in rank order, splits in index order.  No
 // atomics, so the result is bit-identical from run to run.
+#include <cstdlib>
 #include "roast_internal.hpp"
 
 namespace roast {
@@ -106,22 +107,26 @@ __global__ __launch_bounds__(256) void k_dm_scatter(MMArgs a, int splits, int ro
   __syncthreads();
   const int64_t off = s_off;
   const float scale = s_scale;
-  const int q4 = a.Z2 / 4;                                  // float4 groups per tile row
-  const int n4 = min(rows_per_wg, a.Z1 - r_begin) * q4;
+  const int n = min(rows_per_wg, a.Z1 - r_begin) * a.Z2;
   const int64_t plane = a.H * a.O;
-  typedef float vf4 __attribute__((ext_vector_type(4)));
-  for (int e = threadIdx.x; e < n4; e += 256) {
-    const int r = r_begin + e / q4, c = (e % q4) * 4;
+  // Consecutive lanes take consecutive weights: the loads coalesce and each wave's atomics fall in
+  // as few cache lines as possible.  The workspace is read once: non-temporal loads, the splits of
+  // one element in flight together.
+  for (int e = threadIdx.x; e < n; e += 256) {
+    const int r = r_begin + e / a.Z2, c = e % a.Z2;
     const int64_t h = (int64_t)x * a.Z1 + r, o = (int64_t)y * a.Z2 + c;
     if (h >= a.H || o >= a.O) continue;
     const float* g = G + h * a.O + o;
-    vf4 acc = *reinterpret_cast<const vf4*>(g);
-    for (int s = 1; s < splits; ++s) acc += *reinterpret_cast<const vf4*>(g + (int64_t)s * plane);
-    float* d = dM + off + (int64_t)a.Z2 * r + c;
-    unsafeAtomicAdd(d + 0, scale * acc.x);
-    unsafeAtomicAdd(d + 1, scale * acc.y);
-    unsafeAtomicAdd(d + 2, scale * acc.z);
-    unsafeAtomicAdd(d + 3, scale * acc.w);
+    auto ld = [&](int s) { return __builtin_nontemporal_load(g + (int64_t)s * plane); };
+    float acc = 0.f;
+    int s = 0;
+    for (; s + 8 <= splits; s += 8) {
+      const float v0 = ld(s), v1 = ld(s + 1), v2 = ld(s + 2), v3 = ld(s + 3);
+      const float v4 = ld(s + 4), v5 = ld(s + 5), v6 = ld(s + 6), v7 = ld(s + 7);
+      acc += ((v0 + v1) + (v2 + v3)) + ((v4 + v5) + (v6 + v7));
+    }
+    for (; s < splits; ++s) acc += ld(s);
+    unsafeAtomicAdd(dM + off + (int64_t)a.Z2 * r + c, scale * acc);
   }
 }
 
@@ -130,12 +135,8 @@ __global__ __launch_bounds__(256) void k_dm_scatter(MMArgs a, int splits, int ro
 // ---- split products through the workspace, then one scatter (the fast path of the ATOMIC mode when
 // the caller provides a workspace): S*H*O floats.
 int dm_ws_splits(const MMArgs& a) {
-  if (a.Z2 % 4 != 0 || a.O % 4 != 0) return 0;
-  const int64_t tiles = ((a.H + 255) / 256) * ((a.O + 127) / 128);
-  int64_t s = (512 + tiles - 1) / tiles;
-  const int64_t cap = (a.I + 255) / 256;
-  if (s > cap) s = cap;
-  return s > 1 ? (int)s : 0;          // a single split gains nothing over direct atomics
+  const int s = dm_pick_splits(((a.H + 255) / 256) * ((a.O + 127) / 128), a.I);
+  return s > 1 ? s : 0;               // a single split gains nothing over direct atomics
 }
 
 size_t dm_ws_workspace_bytes(const MMArgs& a) {
@@ -150,7 +151,7 @@ roast_status dm_ws_run(const MMArgs& a, const void* X, int64_t ldx, const void* 
   float* G = (float*)ws;
   roast_status st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, nullptr, G, splits, s);
   if (st != ROAST_OK) return st;      // UNSUPPORTED: the caller falls back to direct atomics
-  const int rows_per_wg = a.Z2 >= 1024 ? 1 : (int)((4096 / a.Z2) > 0 ? (4096 / a.Z2) : 1);
+  const int rows_per_wg = a.Z2 >= 1024 ? 1 : 1024 / a.Z2;    // four weights per thread
   const int chunks = (a.Z1 + rows_per_wg - 1) / rows_per_wg;
   const int64_t blocks = a.nTx * a.nTy * chunks;
   if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
