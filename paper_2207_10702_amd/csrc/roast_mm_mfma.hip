@@ -56,6 +56,10 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
+// s_waitcnt immediate (gfx9 layout: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8) that
+// waits until at most n vector-memory operations are outstanding and leaves the other counters alone.
+constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
+
 // Byte offset of 16-byte chunk `chunk` (0..7) of row `row` inside an operand tile.
 __device__ inline int lds_off(int row, int chunk) {
   return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
@@ -145,11 +149,11 @@ struct TLoad {
 // Producer side: per-thread addressing context and one register set of staged operand data.
 template <int MODE, int BM, int BN>
 struct ProdCtx {
-  static constexpr int A_LOADS = BM / 32;
+  static constexpr int A_LOADS = BM / 32;     // direct-to-LDS instructions per producer wave and step
   static constexpr int FW_NG = BN / 4, FW_KBS = 256 / FW_NG, FW_BLK = 8 / FW_KBS;
   static constexpr int DX_LOADS = BN / 32;
   int ptid;
-  // FWD / DX, A operand: BM rows x 8 chunks; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
+  // FWD / DX, A operand: source of this lane for each of the wave's direct-to-LDS loads
   const uint16_t* a_ptr[MODE == MODE_DM ? 1 : A_LOADS];
   // FWD, B operand: 8(k) x 4(n) fp32 blocks; thread -> column group ptid % FW_NG, k-blocks ptid / FW_NG + FW_KBS*b
   int fw_yl, fw_nin;
@@ -163,7 +167,6 @@ struct ProdCtx {
 template <int MODE, int BM, int BN, bool SHADOW>
 struct RegSet {
   using Ctx = ProdCtx<MODE, BM, BN>;
-  uint4v a_reg[MODE == MODE_DM ? 1 : Ctx::A_LOADS];
   // weight tile from fp32 M ...
   floatx4 fw_reg[(MODE == MODE_FWD && !SHADOW) ? Ctx::FW_BLK * 8 : 1];
   float fw_sgn;
@@ -183,30 +186,41 @@ struct RegSet {
 #endif
 
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
-__global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
-  static_assert(WGM * WGN == 4, "4 consumer waves");
+__global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p) {
+  constexpr int NC = WGM * WGN;                  // consumer waves; waves NC .. NC+3 are the producers
+  constexpr int NT = (NC + 4) * 64;              // threads of the workgroup
+  static_assert(NC == 4 || NC == 8, "one or two consumer waves per SIMD");
   using Ctx = ProdCtx<MODE, BM, BN>;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // consumer wave tile
   constexpr int MI = WTM / 32, NI = WTN / 32;    // 32x32 blocks per wave
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128;
   constexpr int EPI_STRIDE = WTN * 2 + 16;       // bytes per row of a wave's epilogue buffer
-  constexpr int EPI_BYTES = 4 * 32 * EPI_STRIDE;
-  constexpr int NA = 2;                          // LDS stages per operand
+  constexpr int EPI_BYTES = NC * 32 * EPI_STRIDE; // aliases the operand stages once the contraction is done
+  // Forward / dX: the activation operand needs no conversion, so it goes from global memory
+  // straight into LDS (global_load_lds, no registers, no ds_write) through three stages; the weight
+  // operand and both operands of dM pass through registers into two stages.
+  constexpr bool ADMA = (MODE != MODE_DM);
+  constexpr int NA = ADMA ? 3 : 2;               // LDS stages of the A operand
   constexpr int TILES_BYTES = NA * A_BYTES + 2 * B_BYTES;
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  int64_t* s_off = reinterpret_cast<int64_t*>(smem + TILES_BYTES + EPI_BYTES);
-  float* s_sgn = reinterpret_cast<float*>(smem + TILES_BYTES + EPI_BYTES + kMaxTable * 8);
+  static_assert(EPI_BYTES <= TILES_BYTES, "epilogue staging must fit in the operand stages");
+  int64_t* s_off = reinterpret_cast<int64_t*>(smem + TILES_BYTES);
+  float* s_sgn = reinterpret_cast<float*>(smem + TILES_BYTES + kMaxTable * 8);
   auto a_stage = [&](int step) -> char* { return smem + (step % NA) * A_BYTES; };
   auto b_stage = [&](int step) -> char* { return smem + NA * A_BYTES + (step & 1) * B_BYTES; };
 
   const MMArgs& a = p.a;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const bool producer = wave >= 4;
+  const bool producer = wave >= NC;
   const int I = (int)a.I;
   int bx, by, bz;
   if (!block_coords(p, &bx, &by, &bz)) return;   // whole workgroup leaves before any barrier
   const int m0 = by * BM, n0 = bx * BN;
+#ifdef ROAST_EXP_CLK
+  unsigned long long clk0 = 0, wall0 = 0;
+  if (blockIdx.x == 300 && p.dM != nullptr && MODE != MODE_DM && threadIdx.x == 0) { clk0 = clock64(); wall0 = wall_clock64(); }
+#endif
 #ifdef ROAST_EXP_TRACE
   const bool trace_on = (blockIdx.x == 300) && p.dM != nullptr && MODE != MODE_DM;
   unsigned long long* trace_buf = reinterpret_cast<unsigned long long*>(p.dM);
@@ -224,7 +238,7 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
   const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
 #endif
 
-  // ---- tile table (all 512 threads)
+  // ---- tile table (all threads)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
   // DX : entry [kt * TN + xl] for tile (x = n0/Z1 + xl, y = kt), TN = tiles spanned by BN along H
   // DM : entry [xl * TN + yl] for tile (x = m0/Z1 + xl, y = n0/Z2 + yl)
@@ -244,7 +258,7 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
       cnt = ((min(m0 + BM, (int)a.H) - 1) / a.Z1 - x0 + 1) * TN;
     }
-    for (int e = tid; e < cnt; e += 512) {
+    for (int e = tid; e < cnt; e += NT) {
       uint64_t x, y;
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
       else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
@@ -268,13 +282,35 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
     // consumer sits at the barrier (measured: the two phases then serialise).
     __builtin_amdgcn_s_setprio(3);
     Ctx c;
-    c.ptid = tid - 256;
+    c.ptid = tid - NC * 64;
     const int pt = c.ptid;
-    if (MODE != MODE_DM) {
+    // A operand: producer wave w copies rows w*BM/4 .. +BM/4 of the tile, 8 rows per instruction.
+    // A direct-to-LDS load puts lane l's 16 bytes at (LDS base) + 16*l, i.e. row l/8, physical chunk
+    // l%8 of that 8-row group -- so the lane fetches the logical chunk the XOR swizzle keeps there.
+    if (ADMA) {
 #pragma unroll
-      for (int q = 0; q < Ctx::A_LOADS; ++q)
-        c.a_ptr[q] = p.A + (int64_t)min(m0 + (pt >> 3) + 32 * q, I - 1) * p.lda + 8 * (pt & 7);
+      for (int q = 0; q < Ctx::A_LOADS; ++q) {
+        const int r = (wave - NC) * (BM / 4) + q * 8 + (lane >> 3);
+        const int ch = (lane ^ r ^ (r >> 3)) & 7;
+        c.a_ptr[q] = p.A + (int64_t)min(m0 + r, I - 1) * p.lda + 8 * ch;
+      }
     }
+    // Always issued (a step past the end is clamped and lands in a stage nobody reads any more), so
+    // that the in-order wait counts below are the same in every iteration.
+    auto dma_issue = [&](int step) {
+      if constexpr (ADMA) {
+#ifdef ROAST_EXP_NODMA
+        if (step > 2) return;
+#endif
+        const int k0 = k_begin + min(step, nsteps - 1) * BK;
+        char* dst = a_stage(step) + (wave - NC) * (BM / 4) * 128;
+#pragma unroll
+        for (int q = 0; q < Ctx::A_LOADS; ++q)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(c.a_ptr[q] + k0),
+                                           (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
     if (MODE == MODE_FWD) {
       const int n = min(n0 + 4 * (pt % Ctx::FW_NG), (int)a.O - 4);
       c.fw_yl = n / a.Z2 - n0 / a.Z2;
@@ -298,10 +334,6 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
 #ifdef ROAST_EXP_NOLOAD
       if (step > 1) return;
 #endif
-      if (MODE != MODE_DM) {
-#pragma unroll
-        for (int q = 0; q < Ctx::A_LOADS; ++q) r.a_reg[q] = *reinterpret_cast<const uint4v*>(c.a_ptr[q] + k0);
-      }
       // Keep the issue order of the load groups the same everywhere (prologue and loop): the wait
       // counters are in-order, and a differing order would make the waits before the LDS writes
       // cover the newest loads as well.
@@ -361,11 +393,6 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
 #endif
       char* At = a_stage(step);
       char* Bt = b_stage(step);
-      if (MODE != MODE_DM) {
-#pragma unroll
-        for (int q = 0; q < Ctx::A_LOADS; ++q)
-          *reinterpret_cast<uint4v*>(At + lds_off((pt >> 3) + 32 * q, pt & 7)) = r.a_reg[q];
-      }
       if (MODE == MODE_FWD && SHADOW) {
         // flipping the sign bit of a bf16 equals rounding the negated fp32 value
         const uint32_t flip = r.fw_sgn < 0.f ? 0x80008000u : 0u;
@@ -414,16 +441,44 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
       }
     };
 
-    // Barrier s publishes stage (s & 1) holding step s.  Filling stage (s & 1) for step s is safe
-    // once barrier s-1 has been passed: the consumers finished reading it (step s-2) before that.
-    // Loads run NSETS steps ahead of their use (one register set per step in flight): with a step
-    // of ~0.5 us and a loaded memory latency of 1-2 us, two sets leave the producers latency-bound.
+    // Barrier s publishes step s: its weight tile in B stage (s & 1), written through registers
+    // between barriers s-1 and s (the consumers finished reading that stage, step s-2, before
+    // barrier s-1), and -- forward / dX -- its activation tile in A stage (s % 3), whose
+    // direct-to-LDS loads were issued one iteration earlier (after barrier s-2, when the consumers
+    // had finished step s-3) and are waited for just before barrier s.
+    // Register loads run NSETS steps ahead of their use (one register set per step in flight).
     // The loop body is branch-free (a step index past the end is clamped and its data never
-    // stored) so that the wait for the oldest set can leave the newer loads in flight.
-    constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : 4;   // fp32 weight tiles take twice the registers
+    // stored) so that the in-order wait counts can leave the newer loads in flight:
+    //   issue order in iteration s:  A(s+1) [A_LOADS], B(s+NSETS) [B_LOADS]
+    //   A(s) must have landed before barrier s; younger than it are B(s-1+NSETS), A(s+1), B(s+NSETS).
+    // fp32 weight tiles take twice the registers; twelve waves leave 168 registers per lane
+    constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : (NC == 8 ? 3 : 4);
+    constexpr int B_LOADS = MODE == MODE_FWD ? Ctx::FW_BLK * 8
+                          : (MODE == MODE_DX ? Ctx::DX_LOADS * (SHADOW ? 1 : 2) : 0);
+    static_assert(Ctx::A_LOADS + 2 * B_LOADS < 64, "vmcnt is a 6-bit counter");
+    // The usual barrier (fence + s_barrier) would wait for every outstanding direct-to-LDS load.
+    // What barrier s has to publish is this wave's LDS writes (lgkmcnt 0) and A(s) (the vmcnt
+    // above); the younger loads stay in flight across it.
+    auto barrier_main = [&]() {
+      if constexpr (ADMA) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS + 2 * B_LOADS) & ~0x0f00);
+        __builtin_amdgcn_s_barrier();
+      } else {
+        __syncthreads();
+      }
+    };
+    auto barrier_tail = [&]() {         // no register loads are issued any more: only A(s+1) is younger
+      if constexpr (ADMA) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS) & ~0x0f00);
+        __builtin_amdgcn_s_barrier();
+      } else {
+        __syncthreads();
+      }
+    };
     RegSet<MODE, BM, BN, SHADOW> rs[NSETS];
     const int last = nsteps - 1;
     if (nsteps > 0) {
+      dma_issue(0);
 #pragma unroll
       for (int j = 0; j < NSETS; ++j) load_global(rs[j], min(j, last));
     }
@@ -432,19 +487,27 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
 #pragma unroll
       for (int j = 0; j < NSETS; ++j) {
         TRACE(3 * (s + j) + 0);
+        dma_issue(s + j + 1);
         store_lds(rs[j], s + j);
         TRACE(3 * (s + j) + 1);
         load_global(rs[j], min(s + j + NSETS, last));
         TRACE(3 * (s + j) + 2);
-        __syncthreads();                                 // barrier s + j
+        barrier_main();                                  // barrier s + j
       }
     }
 #pragma unroll
     for (int j = 0; j < NSETS - 1; ++j) {                // remaining steps (fewer than NSETS)
       if (s + j < nsteps) {
+        dma_issue(s + j + 1);
         store_lds(rs[j], s + j);
-        __syncthreads();
+        barrier_tail();
       }
+    }
+    // Nothing may still be on its way to LDS when the consumers start to reuse the stages for
+    // the epilogue (and when the waves end); the barrier pairs with the consumers' one below.
+    if constexpr (ADMA) {
+      __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+      __builtin_amdgcn_s_barrier();
     }
     return;
   }
@@ -470,6 +533,9 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
     const char* Bt = b_stage(s);
     bf16x8 af[2][MI], bfr[2][NI];
     auto fetch = [&](int ks, int buf) {
+#ifdef ROAST_EXP_NOFRAG
+      if (s > 0) return;
+#endif
 #pragma unroll
       for (int i = 0; i < MI; ++i) af[buf][i] = frag(At, wm * WTM + i * 32, ks, lane);
 #pragma unroll
@@ -496,12 +562,19 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
     }
     TRACE(3 * s + 2);
   }
-  // ---- epilogue (consumer waves only; the producers have left)
+#ifdef ROAST_EXP_CLK
+  if (blockIdx.x == 300 && p.dM != nullptr && MODE != MODE_DM && threadIdx.x == 0) {
+    unsigned long long* tb = reinterpret_cast<unsigned long long*>(p.dM);
+    tb[0] = clk0; tb[1] = clock64(); tb[2] = wall0; tb[3] = wall_clock64();
+  }
+#endif
+  // ---- epilogue (consumer waves only)
   if (MODE != MODE_DM) {
+    __syncthreads();   // every wave is done with the operand stages: they become the staging buffers
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
     // Each wave stages one 32-row block at a time in its own LDS buffer and writes it out 16 bytes
     // per lane, row-contiguous.
-    char* ebuf = smem + TILES_BYTES + wave * (32 * EPI_STRIDE);
+    char* ebuf = smem + wave * (32 * EPI_STRIDE);
     constexpr int CPR = WTN / 8;              // 16-byte chunks per row of the wave tile
     constexpr int RPI = 64 / CPR;             // rows per store instruction
 #pragma unroll
@@ -560,10 +633,8 @@ __global__ __launch_bounds__(512) void k_roast_mfma(KernArgs p) {
   }
 }
 
-template <int MODE, int BM, int BN, int WGN>
-constexpr int smem_bytes() {
-  return (2 * BM + 2 * BN) * 128 + 4 * 32 * ((BN / WGN) * 2 + 16) + kMaxTable * 12;
-}
+template <int MODE, int BM, int BN>
+constexpr int smem_bytes() { return ((MODE != MODE_DM ? 3 : 2) * BM + 2 * BN) * 128 + kMaxTable * 12; }
 
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
 roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
@@ -571,7 +642,7 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
   p.nbx = (int)blocks.x; p.nby = (int)blocks.y; p.nbz = (int)blocks.z;
   const dim3 grid((unsigned)((total + 7) / 8 * 8));
-  constexpr int smem = smem_bytes<MODE, BM, BN, WGN>();
+  constexpr int smem = smem_bytes<MODE, BM, BN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool configured = false;   // one attribute call per instantiation per process
   if (!configured) {
@@ -580,7 +651,7 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3(512), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + 4) * 64), smem, s, p);
   return hip_status(hipGetLastError());
 }
 
@@ -594,7 +665,7 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 }  // namespace
 
-#ifdef ROAST_EXP_TRACE
+#if defined(ROAST_EXP_TRACE) || defined(ROAST_EXP_CLK)
 void* g_roast_trace = nullptr;
 extern "C" void roast_set_trace(void* p) { g_roast_trace = p; }
 #endif
@@ -616,11 +687,11 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)Y; p.ldc = ldy;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
-#ifdef ROAST_EXP_TRACE
+#if defined(ROAST_EXP_TRACE) || defined(ROAST_EXP_CLK)
   { extern void* g_roast_trace; p.dM = (float*)g_roast_trace; }
 #endif
-  if (M_bf16) return launch<MODE_FWD, BM, BN, 2, 2, true>(p, grid, s);
-  return launch<MODE_FWD, BM, BN, 2, 2, false>(p, grid, s);
+  if (M_bf16) return launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s);
+  return launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
 }
 
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
@@ -633,8 +704,8 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)dX; p.ldc = ldx;
   const dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
-  if (M_bf16) return launch<MODE_DX, BM, BN, 2, 2, true>(p, grid, s);
-  return launch<MODE_DX, BM, BN, 2, 2, false>(p, grid, s);
+  if (M_bf16) return launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s);
+  return launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
 }
 
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
@@ -645,14 +716,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
     return ROAST_ERR_UNSUPPORTED;
   if ((cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   const int64_t tiles = cdiv(a.H, BM) * cdiv(a.O, BN);
-  if (Gws == nullptr) {
-    // enough workgroups to fill 256 CUs twice over, but at least 4 contraction steps each
-    int64_t want = cdiv(512, tiles);
-    const int64_t cap = cdiv(a.I, 4 * BK);
-    if (want > cap) want = cap;
-    if (want < 1) want = 1;
-    splits = (int)want;
-  }
+  if (Gws == nullptr) splits = dm_pick_splits(tiles, a.I);
   if (splits < 1 || splits > 65535) return ROAST_ERR_UNSUPPORTED;
   int64_t rows = cdiv(a.I, splits);
   rows = cdiv(rows, BK) * BK;
