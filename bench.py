@@ -26,6 +26,12 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 bf16 FLOP/clk/CU x 2.4 GHz, dense
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this script, each
+# scaled by what the counter reads for a plain 256 MiB copy; profiles/bench_default_pmc_hbm_traffic.txt).
+# Valid for the default workload only.
+MEASURED_TRAFFIC_BYTES = {"mm_fwd_l1": 63.9e6, "mm_fwd_l2": 63.9e6, "mm_bwd_dx_l1": 63.9e6, "mm_bwd_dx_l2": 63.9e6,
+                          "embed_fwd": 1186.0e6}
+
 
 def parse():
     p = argparse.ArgumentParser()
@@ -36,6 +42,9 @@ def parse():
     p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
     p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
     p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
+    p.add_argument("--calibration-copy", action="store_true",
+                   help="profiling aid: also launch one plain 256 MiB device copy per step, the kernel of known "
+                        "size that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     return p.parse_args()
 
 
@@ -85,6 +94,11 @@ def main():
     edM = torch.zeros(ecfg.m_size, dtype=torch.float32, device="cuda")
     ews = torch.empty(max(roast.roast_embed_bwd_workspace(ed, N), 1), dtype=torch.uint8, device="cuda")
 
+    cal_src = cal_dst = None
+    if args.calibration_copy:
+        cal_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        cal_dst = torch.empty_like(cal_src)
+
     names = []
     if not args.embed_only:
         names += ["m_shadow", "mm_fwd_l1", "mm_fwd_l2", "mm_bwd_dx_l2", "mm_bwd_dM_l2", "mm_bwd_dx_l1", "mm_bwd_dM_l1"]
@@ -112,6 +126,8 @@ def main():
         if not args.mm_only:
             roast.roast_embed_fwd(ed, rows, tables, eM, out); mark()
             roast.roast_embed_bwd(ed, rows, tables, dOut, edM, ws=ews); mark()
+        if cal_src is not None:
+            cal_dst.copy_(cal_src)
 
     for _ in range(args.warmup):
         step()
@@ -144,10 +160,14 @@ def main():
         result["value"] = tflops
         result["mm_ms"] = mm_ms
         result["pct_mfma_peak"] = 100.0 * tflops / PEAK_BF16_TFLOPS
-        dom = max((k for k in per_call if k.startswith("mm_")), key=lambda k: per_call[k])
+        # The dominant kernel of the MM path is the MFMA kernel template (forward, dX and the dM
+        # products are its three modes).  A forward / dX call is exactly one launch of it, so the
+        # call's event time is the kernel's duration; the slowest of those four launches is reported.
+        dom = max((k for k in per_call if k.startswith(("mm_fwd", "mm_bwd_dx"))), key=lambda k: per_call[k])
         ach = flop_layer[dom[-2:]] / (per_call[dom] * 1e-3) / 1e12
-        result["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                              "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+        result["roofline"] = {"kernel": "k_roast_mfma (" + dom + ")", "bound": "mfma", "achieved": ach,
+                              "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                              "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
     if not args.mm_only:
         # compulsory HBM bytes: output (or dOut) once, ids once, M (and dM read+write) once
         ids = N * (8 + 4)
@@ -158,9 +178,9 @@ def main():
         tot = (bytes_fwd + bytes_bwd) / ((per_call["embed_fwd"] + per_call["embed_bwd"]) * 1e-3) / 1e9
         result["embedding"] = {"value": tot, "unit": "GB/s", "pct_hbm_peak": 100.0 * tot / PEAK_HBM_GBS,
                                "fwd_GBs": gbs_f, "bwd_GBs": gbs_b, "bytes_fwd": bytes_fwd, "bytes_bwd": bytes_bwd,
-                               "roofline": {"kernel": "embed_fwd", "bound": "hbm", "achieved": gbs_f,
+                               "roofline": {"kernel": "k_embed (embed_fwd)", "bound": "hbm", "achieved": gbs_f,
                                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
-                                            "traffic": None}}
+                                            "traffic": MEASURED_TRAFFIC_BYTES.get("embed_fwd")}}
         if args.embed_only:
             result["value"] = tot
             result["unit"] = "GB/s"

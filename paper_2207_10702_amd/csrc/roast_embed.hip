@@ -195,7 +195,6 @@ inline BucketPlan bucket_plan(const EmbedArgs& a) {
          a.C <= kMaxC;
   if (!p.ok) return p;
   int r = 12;
-  if (const char* e = getenv("ROAST_EMBED_RLOG2")) r = atoi(e);   // tuning aid
   while ((1 << r) < kMaxR && ((a.m_size + (1ll << r) - 1) >> r) > kMaxBuckets) ++r;
   p.r_log2 = r;
   p.nb = (int)((a.m_size + (1ll << r) - 1) >> r);
@@ -341,11 +340,7 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
     vfloat4 d[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-#ifdef ROAST_EXP_NODOUT
-      d[u] = vfloat4{1.f, 2.f, 3.f, (float)e[u].x};
-#else
       d[u] = __builtin_nontemporal_load(reinterpret_cast<const vfloat4*>(dOut + (int64_t)e[u].x * a.Z) + sub);
-#endif
     }
     fetch_entries(i0 + U * ipp + which, en);
 #pragma unroll
@@ -353,22 +348,15 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
       const bool ok = e[u].y != 0xffffffffu;
       const float sc = !ok ? 0.f : ((e[u].y & 0x80000000u) ? -a.lambda : a.lambda);
       const int rel = (ok ? (int)((int64_t)(e[u].y & 0x7fffffffu) - slot0) : 0) + 4 * sub;
-#ifdef ROAST_EXP_NOLDSATOMIC
-      if (d[u].x + d[u].y + d[u].z + d[u].w == 1234.5f) img[rel] = sc;
-#else
       atomicAdd(&img[rel + 0], (double)(sc * d[u].x));
       atomicAdd(&img[rel + 1], (double)(sc * d[u].y));
       atomicAdd(&img[rel + 2], (double)(sc * d[u].z));
       atomicAdd(&img[rel + 3], (double)(sc * d[u].w));
-#endif
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < span; i += 256) {
     const float v = (float)img[i];
-#ifdef ROAST_EXP_NOFLUSH
-    if (v == 1234.5f)
-#endif
     if (v != 0.f && slot0 + i < a.m_size) unsafeAtomicAdd(dM + slot0 + i, v);
   }
 }

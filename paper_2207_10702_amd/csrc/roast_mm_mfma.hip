@@ -2,28 +2,34 @@
 // arXiv 2207.10702): forward Y = X*W, dX = dY*W^T and the per-tile products of dM = scatter(X^T*dY),
 // with W recovered from M tile by tile and never written to memory.
 //
-// One workgroup = 512 threads = 8 waves computes a BM x BN block of the output.  The waves are
-// specialised: waves 0-3 (WGM x WGN) are consumers, each owning a (BM/WGM) x (BN/WGN) sub-block in
-// fp32 accumulators and doing nothing but ds_read_b128 + v_mfma_f32_32x32x16_bf16; waves 4-7 are
-// producers that fetch the next operands from global memory into registers (two register sets,
-// i.e. two contraction steps ahead), sign / round / transpose them and fill the other LDS stage.
-// Each SIMD then holds one consumer and one producer wave, and the hardware interleaves the
-// producer's VMEM / VALU / LDS-write instructions between the consumer's MFMAs.  The contraction
-// runs in steps of BK = 64 through two LDS stages with one workgroup barrier per step.
+// One workgroup computes a BM x BN = 256 x 128 block of the output with specialised waves: the
+// first NC waves are consumers, each owning a (BM/WGM) x (BN/WGN) sub-block in fp32 accumulators and
+// doing nothing but ds_read_b128 + v_mfma_f32_32x32x16_bf16; the last four waves are producers that
+// bring the next operands into LDS.  Forward / dX run eight consumers (two per SIMD, 64 x 64 each, so
+// that one wave's LDS waits hide behind the other's MFMAs) plus the producers, 168 registers per
+// lane; dM runs four consumers (128 x 64 each) because its producers need more registers.  The
+// contraction runs in steps of BK = 64 with one workgroup barrier per step.
 //
 // Both operands sit in LDS as [row][k] with 128-byte rows whose 16-byte chunks are XOR-swizzled,
 // so a lane fetches the 8 contraction values of its row with one conflict-free ds_read_b128
-// (transposing LDS reads were measured at a quarter of that bandwidth).  Whatever is not
-// contraction-contiguous in memory is transposed in registers on its way to LDS:
-//   forward: X rows are copied as they are; the hashed weight tile (fp32, contiguous along O) is
-//            loaded as 8(k) x 4(n) register blocks, signed, rounded to bf16 and written per column;
-//   dX:      dY rows are copied; the tile's rows run along O = the contraction, so it is signed,
-//            rounded and copied row by row;
-//   dM:      contraction is over token rows, so X and dY are both transposed as 8 x 8 (8 x 4)
-//            bf16 blocks with v_perm_b32.
+// (transposing LDS reads were measured at a quarter of that bandwidth).  How an operand gets there:
+//   forward: X rows are contraction-contiguous already: global_load_lds copies them straight into
+//            LDS (three stages; no registers, no ds_write), each lane fetching the chunk the swizzle
+//            wants at its LDS slot.  The hashed weight tile (contiguous along O) is loaded as 8(k) x
+//            4(n) register blocks, signed, rounded to bf16 and written per column (two stages);
+//   dX:      dY rows likewise straight to LDS; the tile's rows run along O = the contraction, so it
+//            is signed, rounded and copied row by row through registers;
+//   dM:      contraction is over token rows, so X and dY are both transposed as 8 x 8 (8 x 4) bf16
+//            blocks with v_perm_b32 on their way through registers (two stages each).
+// Register loads run several steps ahead (one register set per step in flight); the wait counters
+// are in-order, so the producer loop is branch-free and keeps one issue order, and its barriers are
+// raw s_barrier instructions behind explicit s_waitcnt values (the compiler's fence would drain
+// every outstanding direct-to-LDS load).
 // The tile table (offset, sign) of the tiles a workgroup touches is computed by its own threads
 // into LDS at kernel start.  lambda is applied to the fp32 accumulators in the epilogue, which for
-// forward / dX goes through LDS so that global stores are 16 bytes per lane and row-contiguous.
+// forward / dX goes through LDS (the operand stages, free by then) so that global stores are 16
+// bytes per lane and row-contiguous.  Workgroups are numbered so that each XCD's L2 serves a
+// contiguous band of output row blocks.
 #include "roast_internal.hpp"
 
 namespace roast {
@@ -179,11 +185,6 @@ struct RegSet {
   TLoad<MODE == MODE_DM ? BN : 128> tb;
 };
 
-#ifdef ROAST_EXP_TRACE
-#define TRACE(slot) do { if (trace_on && lane == 0 && (slot) < 64) trace_buf[wave * 64 + (slot)] = __builtin_readcyclecounter(); } while (0)
-#else
-#define TRACE(slot) do {} while (0)
-#endif
 
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
 __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p) {
@@ -217,14 +218,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
   int bx, by, bz;
   if (!block_coords(p, &bx, &by, &bz)) return;   // whole workgroup leaves before any barrier
   const int m0 = by * BM, n0 = bx * BN;
-#ifdef ROAST_EXP_CLK
-  unsigned long long clk0 = 0, wall0 = 0;
-  if (blockIdx.x == 300 && p.dM != nullptr && MODE != MODE_DM && threadIdx.x == 0) { clk0 = clock64(); wall0 = wall_clock64(); }
-#endif
-#ifdef ROAST_EXP_TRACE
-  const bool trace_on = (blockIdx.x == 300) && p.dM != nullptr && MODE != MODE_DM;
-  unsigned long long* trace_buf = reinterpret_cast<unsigned long long*>(p.dM);
-#endif
   const int Mdim = MODE == MODE_DM ? (int)a.H : I;
   const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
@@ -232,11 +225,7 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     k_begin = bz * p.rows_per_split;
     k_end = min(I, k_begin + p.rows_per_split);
   }
-#ifdef ROAST_EXP_NOLOOP
-  const int nsteps = 0;
-#else
   const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
-#endif
 
   // ---- tile table (all threads)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
@@ -263,12 +252,8 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
       else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
       else { x = x0 + e / TN; y = y0 + e % TN; }
-#ifdef ROAST_EXP_NOTABLE
-      s_off[e] = (int64_t)(x + y); s_sgn[e] = 1.f;
-#else
       s_off[e] = block_offset(a.hash, a.layer, x, y);
       s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
-#endif
     }
   }
   __syncthreads();
@@ -278,8 +263,8 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     // Loads are unconditional: rows / columns outside the problem are redirected to a valid address
     // and their products are never stored; only the contraction tail of the dM product is zeroed.
     // The producers' instructions are few but on the critical path of every step; with equal
-    // priority the SIMD's arbiter favours the consumer wave and the producer only runs while the
-    // consumer sits at the barrier (measured: the two phases then serialise).
+    // priority the SIMD's arbiter favours the consumer waves and the producer only runs while they
+    // sit at the barrier (measured: the two phases then serialise).
     __builtin_amdgcn_s_setprio(3);
     Ctx c;
     c.ptid = tid - NC * 64;
@@ -299,9 +284,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     // that the in-order wait counts below are the same in every iteration.
     auto dma_issue = [&](int step) {
       if constexpr (ADMA) {
-#ifdef ROAST_EXP_NODMA
-        if (step > 2) return;
-#endif
         const int k0 = k_begin + min(step, nsteps - 1) * BK;
         char* dst = a_stage(step) + (wave - NC) * (BM / 4) * 128;
 #pragma unroll
@@ -331,9 +313,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
 
     auto load_global = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
       const int k0 = k_begin + step * BK;
-#ifdef ROAST_EXP_NOLOAD
-      if (step > 1) return;
-#endif
       // Keep the issue order of the load groups the same everywhere (prologue and loop): the wait
       // counters are in-order, and a differing order would make the waits before the LDS writes
       // cover the newest loads as well.
@@ -388,9 +367,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
 
     auto store_lds = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
       const int k0 = k_begin + step * BK;
-#ifdef ROAST_EXP_NOLDSW
-      if (step > 1) return;
-#endif
       char* At = a_stage(step);
       char* Bt = b_stage(step);
       if (MODE == MODE_FWD && SHADOW) {
@@ -486,12 +462,9 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     for (; s + NSETS <= nsteps; s += NSETS) {
 #pragma unroll
       for (int j = 0; j < NSETS; ++j) {
-        TRACE(3 * (s + j) + 0);
         dma_issue(s + j + 1);
         store_lds(rs[j], s + j);
-        TRACE(3 * (s + j) + 1);
         load_global(rs[j], min(s + j + NSETS, last));
-        TRACE(3 * (s + j) + 2);
         barrier_main();                                  // barrier s + j
       }
     }
@@ -526,16 +499,11 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
   // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
   // Fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued.
   for (int s = 0; s < nsteps; ++s) {
-    TRACE(3 * s + 0);
     __syncthreads();                                     // barrier s: stages hold step s
-    TRACE(3 * s + 1);
     const char* At = a_stage(s);
     const char* Bt = b_stage(s);
     bf16x8 af[2][MI], bfr[2][NI];
     auto fetch = [&](int ks, int buf) {
-#ifdef ROAST_EXP_NOFRAG
-      if (s > 0) return;
-#endif
 #pragma unroll
       for (int i = 0; i < MI; ++i) af[buf][i] = frag(At, wm * WTM + i * 32, ks, lane);
 #pragma unroll
@@ -550,9 +518,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
-#ifdef ROAST_EXP_NOMFMA
-          if (i != 0 || j != 0) continue;
-#endif
           if (MODE == MODE_DM)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
           else
@@ -560,14 +525,7 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
         }
       __builtin_amdgcn_sched_barrier(0);
     }
-    TRACE(3 * s + 2);
   }
-#ifdef ROAST_EXP_CLK
-  if (blockIdx.x == 300 && p.dM != nullptr && MODE != MODE_DM && threadIdx.x == 0) {
-    unsigned long long* tb = reinterpret_cast<unsigned long long*>(p.dM);
-    tb[0] = clk0; tb[1] = clock64(); tb[2] = wall0; tb[3] = wall_clock64();
-  }
-#endif
   // ---- epilogue (consumer waves only)
   if (MODE != MODE_DM) {
     __syncthreads();   // every wave is done with the operand stages: they become the staging buffers
@@ -593,9 +551,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
         const int r = it * RPI + lane / CPR, cc = lane % CPR;
         const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + cc * 16);
         const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 8;
-#ifdef ROAST_EXP_NOSTORE
-        if (v[0] == 0x12345678u)
-#endif
         if (row < Mdim && col < Ndim) *reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col) = v;
       }
     }
@@ -623,9 +578,6 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int r = 8 * (e >> 2) + lr + (e & 3);
-#ifdef ROAST_EXP_NOSTORE
-            if (acc[i][j][e] == 1234567.f)
-#endif
             if (hb + r < (int)a.H && ob + lc < (int)a.O) unsafeAtomicAdd(d + (int64_t)r * a.Z2, sc * acc[i][j][e]);
           }
         }
@@ -665,10 +617,6 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 }  // namespace
 
-#if defined(ROAST_EXP_TRACE) || defined(ROAST_EXP_CLK)
-void* g_roast_trace = nullptr;
-extern "C" void roast_set_trace(void* p) { g_roast_trace = p; }
-#endif
 
 roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s) {
   const int64_t blocks = (m_size + 255) / 256;
@@ -687,9 +635,6 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)Y; p.ldc = ldy;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
-#if defined(ROAST_EXP_TRACE) || defined(ROAST_EXP_CLK)
-  { extern void* g_roast_trace; p.dM = (float*)g_roast_trace; }
-#endif
   if (M_bf16) return launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s);
   return launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
 }

@@ -8,7 +8,6 @@
 // [offset, offset + Z1*Z2) covers j -- a contiguous run of the ranked table because all tiles have
 // the same length -- and adds their contributions in rank order, splits in index order.  No
 // atomics, so the result is bit-identical from run to run.
-#include <cstdlib>
 #include "roast_internal.hpp"
 
 namespace roast {
