@@ -99,7 +99,7 @@ def main():
     N = ecfg.N
     out = torch.empty((N, ecfg.D), dtype=torch.float32, device="cuda")
     edM = torch.zeros(ecfg.m_size, dtype=torch.float32, device="cuda")
-    ews = torch.empty(max(roast.roast_embed_bwd_workspace(ed, N), 1), dtype=torch.uint8, device="cuda")
+    ews = torch.empty(max(roast.roast_embed_bwd_workspace(ed, N, mode), 1), dtype=torch.uint8, device="cuda")
 
     cal_src = cal_dst = None
     if args.calibration_copy:
@@ -132,7 +132,7 @@ def main():
             roast.roast_mm_bwd_dM(d1, X, dH1, dM, mode, ws); mark()
         if not args.mm_only:
             roast.roast_embed_fwd(ed, rows, tables, eM, out); mark()
-            roast.roast_embed_bwd(ed, rows, tables, dOut, edM, ws=ews); mark()
+            roast.roast_embed_bwd(ed, rows, tables, dOut, edM, mode, ews); mark()
         if cal_src is not None:
             cal_dst.copy_(cal_src)
 

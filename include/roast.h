@@ -169,12 +169,21 @@ roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I,
 roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t* rows,
                              const uint32_t* table_ids, const float* M, float* out, void* stream);
 
-/* Bytes of workspace roast_embed_bwd needs (0 = none). */
+/* Bytes of workspace roast_embed_bwd can use for these sizes and mode (0 = none).
+ * ATOMIC: optional -- with it, large batches are first routed by destination (per-bucket lists in
+ * the workspace) and summed in on-chip memory before they touch dM; without it every element is an
+ * fp32 atomic add into dM.  DETERMINISTIC: required. */
 size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_reduce_mode mode);
 
 /*
  * Gradient of the lookup (Section 3.3):  dM[offset(t,r,c) + o] += lambda * sign * dOut[n, c*Z + o].
  * dOut: N x D fp32 (row stride D); dM: m_size fp32, accumulated into.
+ * DETERMINISTIC: every product fl(lambda * sign * dOut[..]) is converted to 64-bit fixed point with a
+ * quantum derived from the largest |dOut| of the call (at least 31 bits below it), summed with
+ * integer atomics -- exact, hence independent of the order -- and added to dM with one rounding per
+ * slot; bit-identical from run to run.  dOut must be finite (an Inf or NaN turns all of dM into NaN).
+ * ws / ws_bytes: device scratch of at least roast_embed_bwd_workspace() bytes (may be NULL / 0 in
+ * ATOMIC mode); its contents on return are unspecified.
  */
 roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t* rows,
                              const uint32_t* table_ids, const float* dOut, float* dM,

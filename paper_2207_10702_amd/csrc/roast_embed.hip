@@ -8,6 +8,9 @@
 // 1 KiB of contiguous output.
 #include <stdlib.h>
 
+#include <algorithm>
+#include <type_traits>
+
 #include "roast_internal.hpp"
 
 namespace roast {
@@ -209,17 +212,87 @@ inline BucketPlan bucket_plan(const EmbedArgs& a) {
   return p;
 }
 
-__global__ __launch_bounds__(256) void k_embed_zero(uint32_t* __restrict__ p, int n) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
+__global__ __launch_bounds__(256) void k_embed_zero(uint32_t* __restrict__ p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = 0u;
 }
 
+// ---- fixed-point accumulation (the DETERMINISTIC mode).  Integer addition is associative, so sums
+// of fixed-point values do not depend on the order in which atomics land.  Every contribution
+// v = fl(+-lambda * dOut[..]) (one fp32 product, the same rounding as the atomic mode) is converted
+// to a multiple of 2^-shift chosen from the largest |dOut| of the call such that |v| * 2^shift <
+// 2^pbits and pbits + ceil(log2(number of chunks)) <= 62: no sum can overflow 64 bits, and the
+// quantum is at least 2^-31 of the largest contribution (finer than fp32 for any realistic batch).
+struct FixedScale {
+  uint32_t absmax_bits;   // max over dOut of the bits of |x| (order-independent: integer max)
+  uint32_t pad[3];
+};
+
+__global__ __launch_bounds__(256) void k_embed_absmax(const float* __restrict__ dOut, int64_t n,
+                                                      FixedScale* __restrict__ fs) {
+  uint32_t m = 0u;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+    m = max(m, __float_as_uint(dOut[i]) & 0x7fffffffu);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, d, 64));
+  if ((threadIdx.x & 63) == 0 && m != 0u) atomicMax(&fs->absmax_bits, m);
+}
+
+// 2^shift as a double; NaN when dOut holds an Inf or NaN (the result is then NaN everywhere).
+__device__ inline double fixed_scale(const FixedScale* fs, float lambda, int pbits) {
+  const uint32_t bits = fs->absmax_bits;
+  if (bits >= 0x7f800000u) return __longlong_as_double(0x7ff8000000000000ll);
+  const float bound = fabsf(lambda) * __uint_as_float(bits);   // every |contribution| <= bound
+  if (!(bound > 0.f)) return 1.0;
+  if (!(bound < __uint_as_float(0x7f800000u))) return __longlong_as_double(0x7ff8000000000000ll);
+  int ex;
+  frexpf(bound, &ex);                                           // bound < 2^ex
+  return ldexp(1.0, pbits - ex);
+}
+
+__device__ inline unsigned long long to_fixed(float v, double scale) {
+  return (unsigned long long)__double2ll_rn((double)v * scale);
+}
+
+inline int fixed_pbits(int64_t n_items) {
+  int lg = 0;
+  while ((1ll << lg) < n_items + 1) ++lg;
+  return 62 - lg;
+}
+
+// One thread per element: any shape, 64-bit integer atomics straight into the accumulator.
+__global__ __launch_bounds__(256) void k_embed_fixed_elem(EmbedArgs a, int pbits, const int64_t* __restrict__ rows,
+                                                          const uint32_t* __restrict__ tables,
+                                                          const float* __restrict__ dOut, const FixedScale* fs,
+                                                          unsigned long long* __restrict__ acc) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= a.N * a.D) return;
+  const double scale = fixed_scale(fs, a.lambda, pbits);
+  const int64_t n = e / a.D, i = e - n * a.D, c = i / a.Z, o = i - c * a.Z;
+  const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
+  const float sc = a.lambda * (float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
+  atomicAdd(acc + off + o, to_fixed(sc * dOut[e], scale));
+}
+
+__global__ __launch_bounds__(256) void k_embed_fixed_finish(int64_t m_size, float lambda, int pbits, const FixedScale* fs,
+                                                            const unsigned long long* __restrict__ acc,
+                                                            float* __restrict__ dM) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= m_size) return;
+  const double scale = fixed_scale(fs, lambda, pbits);
+  if (scale != scale) { dM[i] += __uint_as_float(0x7fc00000u); return; }
+  const long long v = (long long)acc[i];
+  if (v != 0) dM[i] += (float)((double)v / scale);
+}
+
 // entry = (chunk number g, key); key = offset | (negative sign << 31)
+template <bool FIXED>
 __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, int nb, uint32_t cap, int walk,
                                                      const int64_t* __restrict__ rows,
                                                      const uint32_t* __restrict__ tables, uint32_t* __restrict__ cursor,
                                                      uint2* __restrict__ list, const float* __restrict__ dOut,
-                                                     float* __restrict__ dM) {
+                                                     float* __restrict__ dM, int pbits, const FixedScale* fs,
+                                                     unsigned long long* __restrict__ acc) {
   extern __shared__ __attribute__((aligned(16))) uint32_t s_route[];
   const int C = (int)a.C;
   const int rows_wg = kRouteItems / C;
@@ -295,17 +368,29 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
       // list full: add this chunk directly
       const float sc = (e.y & 0x80000000u) ? -a.lambda : a.lambda;
       const float* src = dOut + (int64_t)e.x * a.Z;
-      float* dst = dM + (e.y & 0x7fffffffu);
-      for (int o = 0; o < a.Z; ++o) unsafeAtomicAdd(dst + o, sc * src[o]);
+      if constexpr (FIXED) {
+        const double scale = fixed_scale(fs, a.lambda, pbits);
+        for (int o = 0; o < a.Z; ++o) atomicAdd(acc + (e.y & 0x7fffffffu) + o, to_fixed(sc * src[o], scale));
+      } else {
+        float* dst = dM + (e.y & 0x7fffffffu);
+        for (int o = 0; o < a.Z; ++o) unsafeAtomicAdd(dst + o, sc * src[o]);
+      }
     }
   }
 }
 
+template <bool FIXED>
 __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, uint32_t cap, int segs_per_bucket,
                                                      const uint32_t* __restrict__ cursor, const uint2* __restrict__ list,
-                                                     const float* __restrict__ dOut, float* __restrict__ dM) {
-  // fp64 image: LDS fp32 atomic adds were measured ~20x slower than fp64 ones on this chip
-  extern __shared__ double img[];   // R + Z doubles
+                                                     const float* __restrict__ dOut, float* __restrict__ dM, int pbits,
+                                                     const FixedScale* fs, unsigned long long* __restrict__ acc) {
+  // fp64 image: LDS fp32 atomic adds were measured ~20x slower than fp64 ones on this chip.
+  // FIXED: the same 8-byte slots hold 64-bit fixed-point sums.
+  using img_t = typename std::conditional<FIXED, unsigned long long, double>::type;
+  extern __shared__ __attribute__((aligned(8))) char img_raw[];
+  img_t* img = reinterpret_cast<img_t*>(img_raw);   // R + Z slots
+  double scale = 0.0;
+  if constexpr (FIXED) scale = fixed_scale(fs, a.lambda, pbits);
   const int b = blockIdx.x / segs_per_bucket, seg = blockIdx.x % segs_per_bucket;
   const uint32_t count = min(cursor[b], cap);
   const uint32_t first = (uint32_t)seg * kSeg;
@@ -314,7 +399,7 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
   const uint2* lst = list + (size_t)b * cap;
   const int R = 1 << r_log2, span = R + a.Z;
   const int64_t slot0 = (int64_t)b << r_log2;
-  for (int i = threadIdx.x; i < span; i += 256) img[i] = 0.0;
+  for (int i = threadIdx.x; i < span; i += 256) img[i] = img_t(0);
   __syncthreads();
   const int lpi = a.Z / 4;                       // lanes per chunk
   const int ipp = 256 / lpi;                     // chunks per pass of the workgroup (Z <= 1024)
@@ -348,16 +433,28 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
       const bool ok = e[u].y != 0xffffffffu;
       const float sc = !ok ? 0.f : ((e[u].y & 0x80000000u) ? -a.lambda : a.lambda);
       const int rel = (ok ? (int)((int64_t)(e[u].y & 0x7fffffffu) - slot0) : 0) + 4 * sub;
-      atomicAdd(&img[rel + 0], (double)(sc * d[u].x));
-      atomicAdd(&img[rel + 1], (double)(sc * d[u].y));
-      atomicAdd(&img[rel + 2], (double)(sc * d[u].z));
-      atomicAdd(&img[rel + 3], (double)(sc * d[u].w));
+      if constexpr (FIXED) {
+        atomicAdd(&img[rel + 0], to_fixed(sc * d[u].x, scale));
+        atomicAdd(&img[rel + 1], to_fixed(sc * d[u].y, scale));
+        atomicAdd(&img[rel + 2], to_fixed(sc * d[u].z, scale));
+        atomicAdd(&img[rel + 3], to_fixed(sc * d[u].w, scale));
+      } else {
+        atomicAdd(&img[rel + 0], (double)(sc * d[u].x));
+        atomicAdd(&img[rel + 1], (double)(sc * d[u].y));
+        atomicAdd(&img[rel + 2], (double)(sc * d[u].z));
+        atomicAdd(&img[rel + 3], (double)(sc * d[u].w));
+      }
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < span; i += 256) {
-    const float v = (float)img[i];
-    if (v != 0.f && slot0 + i < a.m_size) unsafeAtomicAdd(dM + slot0 + i, v);
+    if constexpr (FIXED) {
+      const unsigned long long v = img[i];
+      if (v != 0ull && slot0 + i < a.m_size) atomicAdd(acc + slot0 + i, v);
+    } else {
+      const float v = (float)img[i];
+      if (v != 0.f && slot0 + i < a.m_size) unsafeAtomicAdd(dM + slot0 + i, v);
+    }
   }
 }
 
@@ -373,39 +470,102 @@ size_t embed_bucket_workspace_bytes(const EmbedArgs& a) {
   return p.ok ? p.total : 0;
 }
 
+namespace {
+
+// route + accumulate; FIXED selects the 64-bit fixed-point variant (fs, acc in the workspace)
+template <bool FIXED>
+roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* rows, const uint32_t* tables,
+                        const float* dOut, float* dM, char* base, int pbits, const FixedScale* fs,
+                        unsigned long long* acc, hipStream_t s) {
+  uint32_t* cursor = (uint32_t*)(base + p.cursor_off);
+  uint2* list = (uint2*)(base + p.list_off);
+  hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, (int64_t)p.nb);
+  const int rows_wg = kRouteItems / (int)a.C;
+  const size_t lds_route = (size_t)kRouteItems * (8 + 4 + 2) + (size_t)3 * p.nb * 4;
+  static bool configured = false;   // per instantiation
+  if (!configured) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048) != hipSuccess)
+      return ROAST_ERR_HIP;
+    configured = true;
+  }
+  hipLaunchKernelGGL(k_embed_route<FIXED>, dim3((unsigned)((a.N + rows_wg - 1) / rows_wg)), dim3(256), lds_route, s, a,
+                     p.r_log2, p.nb, p.cap, walk_ok(a), rows, tables, cursor, list, dOut, dM, pbits, fs, acc);
+  const int segs = (int)((p.cap + kSeg - 1) / kSeg);
+  const size_t lds = ((size_t)(1 << p.r_log2) + a.Z) * 8;
+  hipLaunchKernelGGL(k_embed_accum<FIXED>, dim3((unsigned)(p.nb * segs)), dim3(256), lds, s, a, p.r_log2, p.cap, segs,
+                     cursor, list, dOut, dM, pbits, fs, acc);
+  return hip_status(hipGetLastError());
+}
+
+inline bool bucket_worthwhile(const BucketPlan& p, const float* dOut) {
+  return p.ok && p.n_items >= 65536 && ((uintptr_t)dOut & 15) == 0;
+}
+
+struct DetLayoutE {
+  size_t fs_off, acc_off, bucket_off, total;
+};
+
+inline DetLayoutE det_layout_e(const EmbedArgs& a) {
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  DetLayoutE l{};
+  size_t o = 0;
+  l.fs_off = o;     o += up(sizeof(FixedScale));
+  l.acc_off = o;    o += up((size_t)a.m_size * 8);
+  l.bucket_off = o; o += embed_bucket_workspace_bytes(a);
+  l.total = o;
+  return l;
+}
+
+}  // namespace
+
 roast_status embed_bwd_atomic_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables,
                                      const float* dOut, float* dM, void* ws, size_t ws_bytes, hipStream_t s) {
   const BucketPlan p = bucket_plan(a);
   // small problems, odd shapes, or no workspace: plain atomics straight into dM
-  if (!p.ok || ws == nullptr || ws_bytes < p.total || p.n_items < 65536 || ((uintptr_t)dOut & 15) != 0)
+  if (!bucket_worthwhile(p, dOut) || ws == nullptr || ws_bytes < p.total)
     return launch_embed<true>(a, rows, tables, nullptr, nullptr, dOut, dM, s);
-  char* base = (char*)ws;
-  uint32_t* cursor = (uint32_t*)(base + p.cursor_off);
-  uint2* list = (uint2*)(base + p.list_off);
-  hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, p.nb);
-  const int rows_wg = kRouteItems / (int)a.C;
-  const size_t lds_route = (size_t)kRouteItems * (8 + 4 + 2) + (size_t)3 * p.nb * 4;
-  static bool configured = false;
-  if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route), hipFuncAttributeMaxDynamicSharedMemorySize,
-                            160 * 1024 - 2048) != hipSuccess)
-      return ROAST_ERR_HIP;
-    configured = true;
-  }
-  hipLaunchKernelGGL(k_embed_route, dim3((unsigned)((a.N + rows_wg - 1) / rows_wg)), dim3(256), lds_route, s, a,
-                     p.r_log2, p.nb, p.cap, walk_ok(a), rows, tables, cursor, list, dOut, dM);
-  const int segs = (int)((p.cap + kSeg - 1) / kSeg);
-  const size_t lds = ((size_t)(1 << p.r_log2) + a.Z) * sizeof(double);
-  hipLaunchKernelGGL(k_embed_accum, dim3((unsigned)(p.nb * segs)), dim3(256), lds, s, a, p.r_log2, p.cap, segs, cursor,
-                     list, dOut, dM);
-  return hip_status(hipGetLastError());
+  return bucket_run<false>(a, p, rows, tables, dOut, dM, (char*)ws, 0, nullptr, nullptr, s);
 }
 
-size_t embed_det_workspace_bytes(const EmbedArgs&) { return 0; }
+// DETERMINISTIC: largest |dOut| -> fixed-point scale; zeroed 64-bit accumulator of |M| slots in the
+// workspace; the same route + accumulate pipeline (or one thread per element for the shapes it does
+// not take) with integer atomics; then dM += accumulator / scale, one rounding per slot.
+size_t embed_det_workspace_bytes(const EmbedArgs& a) {
+  if (a.N * a.C >= (1ll << 40)) return 0;
+  return det_layout_e(a).total;
+}
 
-roast_status embed_bwd_det_run(const EmbedArgs&, const int64_t*, const uint32_t*, const float*, float*, void*,
-                               hipStream_t) {
-  return ROAST_ERR_UNSUPPORTED;
+roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
+                               float* dM, void* ws, hipStream_t s) {
+  if (a.N * a.C >= (1ll << 40)) return ROAST_ERR_UNSUPPORTED;
+  const DetLayoutE l = det_layout_e(a);
+  char* base = (char*)ws;
+  FixedScale* fs = (FixedScale*)(base + l.fs_off);
+  unsigned long long* acc = (unsigned long long*)(base + l.acc_off);
+  const int pbits = fixed_pbits(a.N * a.C);
+  // zero the scale record and the accumulator (contiguous: fs_off == 0, acc follows)
+  const int64_t zero_words = (int64_t)((l.acc_off + (size_t)a.m_size * 8) / 4);
+  const int64_t zb = (zero_words + 255) / 256;
+  if (zb > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_embed_zero, dim3((unsigned)zb), dim3(256), 0, s, (uint32_t*)base, zero_words);
+  const int64_t n_el = a.N * a.D;
+  const int64_t ab = std::min<int64_t>((n_el + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(k_embed_absmax, dim3((unsigned)ab), dim3(256), 0, s, dOut, n_el, fs);
+  const BucketPlan p = bucket_plan(a);
+  roast_status st;
+  if (bucket_worthwhile(p, dOut)) {
+    st = bucket_run<true>(a, p, rows, tables, dOut, dM, base + l.bucket_off, pbits, fs, acc, s);
+  } else {
+    const int64_t blocks = (n_el + 255) / 256;
+    if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_embed_fixed_elem, dim3((unsigned)blocks), dim3(256), 0, s, a, pbits, rows, tables, dOut, fs, acc);
+    st = hip_status(hipGetLastError());
+  }
+  if (st != ROAST_OK) return st;
+  hipLaunchKernelGGL(k_embed_fixed_finish, dim3((unsigned)((a.m_size + 255) / 256)), dim3(256), 0, s, a.m_size, a.lambda,
+                     pbits, fs, acc, dM);
+  return hip_status(hipGetLastError());
 }
 
 roast_status chunk_index_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, int64_t* off,

@@ -195,6 +195,16 @@ def test_cfg4_dlrm_lookup_full_size(roast):
     ref_dM = oracle.embed_bwd(ei.hash, cfg.D, cfg.Z, cfg.m_size, float(cfg.lam), ei.rows, ei.tables, ei.dOut)
     assert rel_err(to_host_f64(dM), ref_dM) <= F32_TOL
     assert abs(dot64(dOut, out) - dot64(dM, Md)) <= 1e-4 * abs(dot64(dM, Md))
+    # deterministic mode at full size: parity, and the same bits on a second run
+    det = roast.ROAST_REDUCE_DETERMINISTIC
+    ws_det = torch.empty(roast.roast_embed_bwd_workspace(d, cfg.N, det), dtype=torch.uint8, device="cuda")
+    runs = []
+    for _ in range(2):
+        dM_det = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
+        roast.roast_embed_bwd(d, rows, tables, dOut, dM_det, det, ws_det)
+        runs.append(dM_det.cpu().numpy())
+    assert rel_err(runs[0].astype(np.float64), ref_dM) <= F32_TOL
+    assert np.array_equal(runs[0].view(np.uint32), runs[1].view(np.uint32))
 
 
 # ------------------------------------------------------------------ config 5 (large layer, large M)

@@ -223,3 +223,45 @@ def test_lookup_matches_oracle(roast, D, Z, m, N):
     assert rel_err(to_host_f64(out), ref_out) <= 1e-7
     assert rel_err(to_host_f64(dM), ref_dM) <= F32_TOL
     assert rel_err(to_host_f64(dM_ws), ref_dM) <= F32_TOL
+    # deterministic mode: within tolerance of the oracle, accumulated INTO dM, and bit-identical run to run
+    det = roast.ROAST_REDUCE_DETERMINISTIC
+    ws_det = torch.empty(max(roast.roast_embed_bwd_workspace(d, N, det), 1), dtype=torch.uint8, device="cuda")
+    start = rng.standard_normal(m).astype(np.float32)
+    runs = []
+    for _ in range(3):
+        dM_det = to_dev(start.copy())
+        roast.roast_embed_bwd(d, to_dev(rows), to_dev(tables), to_dev(dOut), dM_det, det, ws_det)
+        runs.append(dM_det.cpu().numpy())
+    assert rel_err(runs[0].astype(np.float64) - start.astype(np.float64), ref_dM) <= F32_TOL
+    assert np.array_equal(runs[0].view(np.uint32), runs[1].view(np.uint32))
+    assert np.array_equal(runs[0].view(np.uint32), runs[2].view(np.uint32))
+
+
+def test_lookup_deterministic_needs_its_workspace(roast):
+    h = wl.draw_hash(np.random.default_rng(3))
+    d = roast.embed_desc(16, 4, 100, 1.0, h)
+    rows = to_dev(np.arange(10, dtype=np.int64))
+    tables = to_dev(np.zeros(10, dtype=np.uint32))
+    dOut = torch.zeros((10, 16), dtype=torch.float32, device="cuda")
+    dM = torch.zeros(100, dtype=torch.float32, device="cuda")
+    assert roast.roast_embed_bwd_workspace(d, 10, roast.ROAST_REDUCE_DETERMINISTIC) > 0
+    with pytest.raises(Exception, match="(?i)workspace"):
+        roast.roast_embed_bwd(d, rows, tables, dOut, dM, roast.ROAST_REDUCE_DETERMINISTIC, None)
+
+
+def test_lookup_deterministic_extremes(roast):
+    """Fixed-point scale from the largest |dOut|: huge and tiny magnitudes, one hot slot, zeros."""
+    rng = np.random.default_rng(11)
+    D, Z, m, N = 8, 4, 40, 3000
+    h = wl.draw_hash(rng)
+    rows = np.zeros(N, dtype=np.int64)                  # every lookup hits the same row: 3000-fold collisions
+    tables = np.zeros(N, dtype=np.uint32)
+    d = roast.embed_desc(D, Z, m, np.float32(1.5), h)
+    det = roast.ROAST_REDUCE_DETERMINISTIC
+    ws = torch.empty(roast.roast_embed_bwd_workspace(d, N, det), dtype=torch.uint8, device="cuda")
+    for scale in (1e30, 1e-30, 1.0, 0.0):
+        dOut = (rng.standard_normal((N, D)) * scale).astype(np.float32)
+        dM = torch.zeros(m, dtype=torch.float32, device="cuda")
+        roast.roast_embed_bwd(d, to_dev(rows), to_dev(tables), to_dev(dOut), dM, det, ws)
+        ref = oracle.embed_bwd(h, D, Z, m, 1.5, rows, tables, dOut)
+        assert rel_err(to_host_f64(dM), ref) <= F32_TOL
