@@ -75,7 +75,7 @@ def main():
     d1 = roast.mm_desc(l1.H, l1.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l1.layer_id, mcfg.lam, mi.hash)
     d2 = roast.mm_desc(l2.H, l2.O, mcfg.Z1, mcfg.Z2, mcfg.m_size, l2.layer_id, mcfg.lam, mi.hash)
     M = to_dev(mi.M)
-    Mb = torch.empty(mcfg.m_size, dtype=torch.bfloat16, device="cuda")
+    Mb = torch.empty(roast.roast_m_shadow_bytes(mcfg.m_size) // 2, dtype=torch.bfloat16, device="cuda")
     X = to_dev(mi.X[l1.name])
     dY = to_dev(mi.dY[l2.name])
     I = mcfg.I

@@ -122,18 +122,21 @@ roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, cons
                                       const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream);
 
 /*
- * bf16 copy of M (round to nearest even), |M|-sized -- never |W|-sized.  Optional: the bf16 kernels
- * stage the weight operand in bfloat16 anyway (see the conventions above), so reading it from this
- * copy gives bit-identical results with half the weight traffic.  Make it once per update of M and
- * pass it to as many roast_mm_fwd / roast_mm_bwd_dx calls as share that M.
- * shadow: DEVICE buffer of m_size 2-byte elements, owned by the caller.
+ * bf16 shadow of M (round to nearest even), about |M|-sized -- never |W|-sized.  Optional: the bf16
+ * kernels stage the weight operand in bfloat16 anyway (see the conventions above), so reading it
+ * from this copy gives bit-identical results with half the weight traffic.  Make it once per update
+ * of M and pass it to as many roast_mm_fwd / roast_mm_bwd_dx calls as share that M.
+ * The buffer holds two copies, the second shifted by one element, so that a tile at an odd offset
+ * can be read with dword-aligned loads as well; its layout is private to the library.
+ * shadow: DEVICE buffer of roast_m_shadow_bytes(m_size) bytes, 16-byte aligned, owned by the caller.
  */
+size_t roast_m_shadow_bytes(int64_t m_size);
 roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream);
 
 /*
  * ROAST-MM forward, Algorithm 1:  Y[I x O] = X[I x H] * W,  W recovered tile by tile from M.
  * X: I x H (ldx), Y: I x O (ldy), both of type `dt`; M: m_size fp32.  Y is overwritten.
- * M_bf16: NULL, or the copy of this M made by roast_m_shadow_bf16 (used by the bf16 kernels only).
+ * M_bf16: NULL, or the shadow of this M made by roast_m_shadow_bf16 (used by the bf16 kernels only).
  */
 roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
                           const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream);

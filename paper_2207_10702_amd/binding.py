@@ -17,7 +17,7 @@ ROAST_F32, ROAST_BF16 = 0, 1
 ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
-           "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
+           "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd"]
 
 
@@ -64,6 +64,8 @@ def load() -> C.CDLL:
     lib.roast_tile_index.argtypes = [MP, vp, vp]
     lib.roast_tile_index_device.argtypes = [MP, vp, vp, vp]
     lib.roast_chunk_index_device.argtypes = [EP, i64, vp, vp, vp, vp, vp]
+    lib.roast_m_shadow_bytes.argtypes = [i64]
+    lib.roast_m_shadow_bytes.restype = C.c_size_t
     lib.roast_m_shadow_bf16.argtypes = [vp, i64, vp, vp]
     lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
@@ -76,7 +78,8 @@ def load() -> C.CDLL:
     lib.roast_embed_bwd.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp, sz, vp]
     for name in EXPORTS:
         f = getattr(lib, name)
-        if name not in ("roast_status_string", "roast_mm_bwd_dM_workspace", "roast_embed_bwd_workspace"):
+        if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
+                        "roast_embed_bwd_workspace"):
             f.restype = i32
     _lib = lib
     return lib
@@ -169,13 +172,19 @@ def roast_chunk_index_device(desc: RoastEmbedDesc, rows, table_ids, stream=None)
     return off, sgn
 
 
+def roast_m_shadow_bytes(m_size: int) -> int:
+    return int(load().roast_m_shadow_bytes(int(m_size)))
+
+
 def roast_m_shadow_bf16(M, shadow=None, stream=None):
-    """bf16 copy of M for the bf16 ROAST-MM kernels (make it once per update of M)."""
+    """bf16 shadow of M for the bf16 ROAST-MM kernels (make it once per update of M); a bfloat16
+    tensor of roast_m_shadow_bytes(|M|) / 2 elements whose layout is private to the library."""
     torch = _torch()
+    n = roast_m_shadow_bytes(M.numel()) // 2
     if shadow is None:
-        shadow = torch.empty(M.numel(), dtype=torch.bfloat16, device=M.device)
-    if shadow.numel() != M.numel():
-        raise ValueError("shadow must have as many elements as M")
+        shadow = torch.empty(n, dtype=torch.bfloat16, device=M.device)
+    if shadow.numel() != n:
+        raise ValueError("shadow must have roast_m_shadow_bytes(|M|) / 2 elements")
     _check(load().roast_m_shadow_bf16(_vec(M, torch.float32, "M"), M.numel(), _vec(shadow, torch.bfloat16, "shadow"),
                                       _stream(stream)), "roast_m_shadow_bf16")
     return shadow
@@ -185,8 +194,8 @@ def _shadow_ptr(M, M_bf16) -> int:
     if M_bf16 is None:
         return 0
     torch = _torch()
-    if M_bf16.numel() != M.numel():
-        raise ValueError("M_bf16 must have as many elements as M")
+    if M_bf16.numel() != roast_m_shadow_bytes(M.numel()) // 2:
+        raise ValueError("M_bf16 must be the tensor made by roast_m_shadow_bf16 for this M")
     return _vec(M_bf16, torch.bfloat16, "M_bf16")
 
 

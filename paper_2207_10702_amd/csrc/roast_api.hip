@@ -98,10 +98,14 @@ roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, cons
   return chunk_index_launch(a, rows, table_ids, off_dev, sgn_dev, (hipStream_t)stream);
 }
 
+size_t roast_m_shadow_bytes(int64_t m_size) {
+  return m_size > 0 ? (size_t)(2 * shadow_stride(m_size)) * 2 : 0;
+}
+
 roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream) {
   if (m_size < 0) return ROAST_ERR_ARG;
   if (m_size == 0) return ROAST_OK;
-  if (!M || !shadow) return ROAST_ERR_ARG;
+  if (!M || !shadow || ((uintptr_t)shadow & 15) != 0) return ROAST_ERR_ARG;
   return shadow_bf16_launch(M, m_size, shadow, (hipStream_t)stream);
 }
 

@@ -87,6 +87,7 @@ roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t 
 // ---- bf16 MFMA kernels (roast_mm_mfma.hip): return ROAST_ERR_UNSUPPORTED when the shape does not
 // meet their divisibility rules; the caller then falls back to the generic kernels.
 // M_bf16 (optional): bf16 copy of M made by shadow_bf16_launch; halves the weight traffic.
+int64_t shadow_stride(int64_t m_size);   // elements between the two copies of the bf16 shadow (a multiple of 64)
 roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s);
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
                          int64_t ldy, hipStream_t s);

@@ -45,11 +45,14 @@ struct __attribute__((packed, aligned(4))) f4u {  // 4 floats, 4-byte aligned (t
   float v[4];
 };
 
-struct __attribute__((packed, aligned(2))) h4u {  // 4 bf16, 2-byte aligned (tile bases in the bf16 shadow of M)
-  uint16_t v[4];
+// 4 / 8 bf16 at a 4-byte aligned address of the bf16 shadow of M.  The shadow holds two copies, the
+// second shifted by one element, so that a tile base of either parity is dword-aligned in one of
+// them: loads that straddle dwords were measured at three times the cost in the texture data path.
+struct __attribute__((packed, aligned(4))) h4a {
+  uint32_t v[2];
 };
-struct __attribute__((packed, aligned(2))) h8u {
-  uint16_t v[8];
+struct __attribute__((packed, aligned(4))) h8a {
+  uint32_t v[4];
 };
 
 constexpr int BK = 64;
@@ -83,7 +86,8 @@ struct KernArgs {
   const uint16_t* B;   // DM: dY
   int64_t ldb;
   const float* M;      // FWD / DX
-  const uint16_t* Mb;  // FWD / DX: bf16 copy of M (SHADOW kernels)
+  const uint16_t* Mb;  // FWD / DX: bf16 shadow of M (SHADOW kernels): copy 0, and copy 1 (shifted by one) at +mb_stride
+  int64_t mb_stride;
   uint16_t* C;         // FWD: Y, DX: dX
   int64_t ldc;
   float* dM;           // DM, atomic mode
@@ -163,6 +167,10 @@ struct ProdCtx {
   const uint16_t* a_ptr[MODE == MODE_DM ? 1 : A_LOADS];
   // FWD, B operand: 8(k) x 4(n) fp32 blocks; thread -> column group ptid % FW_NG, k-blocks ptid / FW_NG + FW_KBS*b
   int fw_yl, fw_nin;
+  // FWD from the bf16 shadow: 4(k) x 8(n) bf16 blocks (16-byte loads); thread -> column group ptid % FS_NG, k-block ptid / FS_NG
+  static constexpr int FS_NG = BN / 8;
+  static_assert(256 / FS_NG * 4 == 64, "one 4 x 8 block per producer thread covers the 64-deep step");
+  int fs_yl, fs_nin;
   // DX, B operand: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
   int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
   int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
@@ -179,7 +187,7 @@ struct RegSet {
   floatx4 dx_reg[(MODE == MODE_DX && !SHADOW) ? Ctx::DX_LOADS * 2 : 1];
   float dx_sgn[MODE == MODE_DX ? Ctx::DX_LOADS : 1];
   // ... or from its bf16 shadow
-  uint2v fs_reg[(MODE == MODE_FWD && SHADOW) ? Ctx::FW_BLK * 8 : 1];
+  uint4v fs_reg[(MODE == MODE_FWD && SHADOW) ? 4 : 1];
   uint4v ds_reg[(MODE == MODE_DX && SHADOW) ? Ctx::DX_LOADS : 1];
   TLoad<MODE == MODE_DM ? BM : 128> ta;
   TLoad<MODE == MODE_DM ? BN : 128> tb;
@@ -297,6 +305,9 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
       const int n = min(n0 + 4 * (pt % Ctx::FW_NG), (int)a.O - 4);
       c.fw_yl = n / a.Z2 - n0 / a.Z2;
       c.fw_nin = n % a.Z2;
+      const int n8 = min(n0 + 8 * (pt % Ctx::FS_NG), (int)a.O - 8);
+      c.fs_yl = n8 / a.Z2 - n0 / a.Z2;
+      c.fs_nin = n8 % a.Z2;
     }
     if (MODE == MODE_DX) {
 #pragma unroll
@@ -317,7 +328,19 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
       // counters are in-order, and a differing order would make the waits before the LDS writes
       // cover the newest loads as well.
       __builtin_amdgcn_sched_barrier(0);
-      if (MODE == MODE_FWD) {
+      if (MODE == MODE_FWD && SHADOW) {
+        const int e = (k0 / a.Z1) * TN + c.fs_yl;
+        const int64_t off0 = s_off[e];
+        const int64_t rel = off0 + (int64_t)a.Z2 * (k0 % a.Z1 + 4 * (pt / Ctx::FS_NG)) + c.fs_nin;
+        // everything added to the tile base is even (Z2 % 8 == 0): the base's parity picks the copy
+        const uint16_t* mb = p.Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);
+        r.fw_sgn = s_sgn[e];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const h8a m = *reinterpret_cast<const h8a*>(mb + rel + (int64_t)q * a.Z2);
+          r.fs_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
+        }
+      } else if (MODE == MODE_FWD) {
         const int e = (k0 / a.Z1) * TN + c.fw_yl;
         const int64_t rel = s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (pt / Ctx::FW_NG)) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
@@ -326,23 +349,18 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
 #pragma unroll
           for (int q = 0; q < 8; ++q) {
             const int64_t at = rel + (int64_t)(8 * Ctx::FW_KBS * b + q) * a.Z2;
-            if constexpr (SHADOW) {
-              const h4u m = *reinterpret_cast<const h4u*>(p.Mb + at);
-              r.fs_reg[b * 8 + q] = uint2v{(uint32_t)m.v[0] | ((uint32_t)m.v[1] << 16),
-                                           (uint32_t)m.v[2] | ((uint32_t)m.v[3] << 16)};
-            } else {
-              const f4u m = *reinterpret_cast<const f4u*>(p.M + at);
-              r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
-            }
+            const f4u m = *reinterpret_cast<const f4u*>(p.M + at);
+            r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
           }
       } else if (MODE == MODE_DX && SHADOW) {
         const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
-          const h8u m = *reinterpret_cast<const h8u*>(p.Mb + s_off[e] + c.dx_rowoff[q] + kin);
-          r.ds_reg[q] = uint4v{(uint32_t)m.v[0] | ((uint32_t)m.v[1] << 16), (uint32_t)m.v[2] | ((uint32_t)m.v[3] << 16),
-                               (uint32_t)m.v[4] | ((uint32_t)m.v[5] << 16), (uint32_t)m.v[6] | ((uint32_t)m.v[7] << 16)};
+          const int64_t off0 = s_off[e];
+          const uint16_t* mb = p.Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);   // row offsets are even (Z2 % 8 == 0)
+          const h8a m = *reinterpret_cast<const h8a*>(mb + off0 + c.dx_rowoff[q] + kin);
+          r.ds_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
           r.dx_sgn[q] = s_sgn[e];
         }
       } else if (MODE == MODE_DX) {
@@ -372,17 +390,14 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
       if (MODE == MODE_FWD && SHADOW) {
         // flipping the sign bit of a bf16 equals rounding the negated fp32 value
         const uint32_t flip = r.fw_sgn < 0.f ? 0x80008000u : 0u;
+        const int kb4 = pt / Ctx::FS_NG;            // k = 4*kb4 .. +3: half a 16-byte chunk per column
 #pragma unroll
-        for (int b = 0; b < Ctx::FW_BLK; ++b)
-#pragma unroll
-          for (int cc = 0; cc < 4; ++cc) {
-            const uint32_t sel = (cc & 1) ? 0x07060302u : 0x05040100u;
-            uint4v o;
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr)
-              o[pr] = __builtin_amdgcn_perm(r.fs_reg[b * 8 + 2 * pr + 1][cc >> 1], r.fs_reg[b * 8 + 2 * pr][cc >> 1], sel) ^ flip;
-            *reinterpret_cast<uint4v*>(Bt + lds_off(4 * (pt % Ctx::FW_NG) + cc, pt / Ctx::FW_NG + Ctx::FW_KBS * b)) = o;
-          }
+        for (int cc = 0; cc < 8; ++cc) {
+          const uint32_t sel = (cc & 1) ? 0x07060302u : 0x05040100u;
+          const uint2v o = {__builtin_amdgcn_perm(r.fs_reg[1][cc >> 1], r.fs_reg[0][cc >> 1], sel) ^ flip,
+                            __builtin_amdgcn_perm(r.fs_reg[3][cc >> 1], r.fs_reg[2][cc >> 1], sel) ^ flip};
+          *reinterpret_cast<uint2v*>(Bt + lds_off(8 * (pt % Ctx::FS_NG) + cc, kb4 >> 1) + 8 * (kb4 & 1)) = o;
+        }
       } else if (MODE == MODE_FWD) {
         const float sg = r.fw_sgn;
 #pragma unroll
@@ -429,7 +444,7 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     //   A(s) must have landed before barrier s; younger than it are B(s-1+NSETS), A(s+1), B(s+NSETS).
     // fp32 weight tiles take twice the registers; twelve waves leave 168 registers per lane
     constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : (NC == 8 ? 3 : 4);
-    constexpr int B_LOADS = MODE == MODE_FWD ? Ctx::FW_BLK * 8
+    constexpr int B_LOADS = MODE == MODE_FWD ? (SHADOW ? 4 : Ctx::FW_BLK * 8)
                           : (MODE == MODE_DX ? Ctx::DX_LOADS * (SHADOW ? 1 : 2) : 0);
     static_assert(Ctx::A_LOADS + 2 * B_LOADS < 64, "vmcnt is a 6-bit counter");
     // The usual barrier (fence + s_barrier) would wait for every outstanding direct-to-LDS load.
@@ -607,9 +622,15 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   return hip_status(hipGetLastError());
 }
 
-__global__ __launch_bounds__(256) void k_shadow_bf16(const float* __restrict__ M, int64_t n, uint16_t* __restrict__ out) {
+// out[i] = bf16(M[i]) and out[stride + i] = bf16(M[i + 1]), zero beyond the end of M
+__global__ __launch_bounds__(256) void k_shadow_bf16(const float* __restrict__ M, int64_t n, int64_t stride,
+                                                     uint16_t* __restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) out[i] = __builtin_bit_cast(uint16_t, (__bf16)M[i]);
+  if (i >= stride) return;
+  const uint16_t cur = i < n ? __builtin_bit_cast(uint16_t, (__bf16)M[i]) : (uint16_t)0;
+  const uint16_t nxt = i + 1 < n ? __builtin_bit_cast(uint16_t, (__bf16)M[i + 1]) : (uint16_t)0;
+  out[i] = cur;
+  out[stride + i] = nxt;
 }
 
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
@@ -618,10 +639,13 @@ inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 }  // namespace
 
 
+int64_t shadow_stride(int64_t m_size) { return (m_size + 1 + 63) / 64 * 64; }
+
 roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s) {
-  const int64_t blocks = (m_size + 255) / 256;
+  const int64_t stride = shadow_stride(m_size);
+  const int64_t blocks = (stride + 255) / 256;
   if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(k_shadow_bf16, dim3((unsigned)blocks), dim3(256), 0, s, M, m_size, (uint16_t*)shadow);
+  hipLaunchKernelGGL(k_shadow_bf16, dim3((unsigned)blocks), dim3(256), 0, s, M, m_size, stride, (uint16_t*)shadow);
   return hip_status(hipGetLastError());
 }
 
@@ -633,9 +657,11 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   constexpr int BM = 256, BN = 128;
   if (a.nTx * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
-  p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)Y; p.ldc = ldy;
+  p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16;
+  p.mb_stride = shadow_stride(a.m_size); p.C = (uint16_t*)Y; p.ldc = ldy;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
-  if (M_bf16) return launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s);
+  // the shadow is read in 8-column pieces, which must not straddle tiles
+  if (M_bf16 && a.Z2 % 8 == 0) return launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s);
   return launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
 }
 
@@ -647,7 +673,8 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   constexpr int BM = 256, BN = 128;
   if (a.nTy * (cdiv(BN, a.Z1) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   KernArgs p{};
-  p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.Mb = (const uint16_t*)M_bf16; p.C = (uint16_t*)dX; p.ldc = ldx;
+  p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.Mb = (const uint16_t*)M_bf16;
+  p.mb_stride = shadow_stride(a.m_size); p.C = (uint16_t*)dX; p.ldc = ldx;
   const dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   if (M_bf16) return launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s);
   return launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
