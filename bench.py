@@ -42,6 +42,10 @@ def parse():
     p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
     p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
     p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
+    p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg3_bert_stack_bf16", "cfg5_large_bf16"],
+                   default="default",
+                   help="default = the headline step (cfg2 ROAST-MM + cfg4 lookup); the others time forward, dX and "
+                        "dM of every layer of another ROAST-MM configuration (a secondary figure, same JSON shape)")
     p.add_argument("--dm-workspace", action="store_true",
                    help="atomic mode only: give roast_mm_bwd_dM its optional scratch (contraction parts x H x O "
                         "floats per call); about 7 %% faster dM, but a buffer of the size of the virtual weights, "
@@ -50,6 +54,62 @@ def parse():
                    help="profiling aid: also launch one plain 256 MiB device copy per step, the kernel of known "
                         "size that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
     return p.parse_args()
+
+
+def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
+    """Forward, dX and dM of every layer of one ROAST-MM configuration, all layers sharing M and dM."""
+    cfg = wl.CONFIGS[args.workload]
+    inp = wl.make_mm_inputs(cfg)
+    bf16 = cfg.dtype == "bf16"
+    M = to_dev(inp.M)
+    Mb = roast.roast_m_shadow_bf16(M) if bf16 else None
+    dM = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
+    layers = []
+    tensors = {}
+    for l in cfg.layers:
+        d = roast.mm_desc(l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size, l.layer_id, cfg.lam, inp.hash)
+        key = (l.H, l.O)
+        if key not in tensors:      # one X / dY per distinct shape, reused by the layers of that shape
+            X, dY = to_dev(inp.X[l.name]), to_dev(inp.dY[l.name])
+            tensors[key] = (X, dY, torch.empty_like(dY), torch.empty_like(X))
+        layers.append((d, l) + tensors[key])
+    ws = None
+    if mode == roast.ROAST_REDUCE_DETERMINISTIC or args.dm_workspace:
+        ws = torch.empty(max(max(roast.roast_mm_bwd_dM_workspace(d, cfg.I, mode) for d, *_ in layers), 1),
+                         dtype=torch.uint8, device="cuda")
+
+    def step():
+        if bf16:
+            roast.roast_m_shadow_bf16(M, Mb)
+        for d, l, X, dY, Y, dX in layers:
+            roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb)
+        for d, l, X, dY, Y, dX in reversed(layers):
+            roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb)
+            roast.roast_mm_bwd_dM(d, X, dY, dM, mode, ws)
+
+    for _ in range(args.warmup):
+        step()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms = e0.elapsed_time(e1) / args.steps
+    flop = 3.0 * sum(2.0 * cfg.I * l.H * l.O for l in cfg.layers)
+    peak = PEAK_BF16_TFLOPS if bf16 else 157.3
+    tflops = flop / (ms * 1e-3) / 1e12
+    return {"metric": "ROAST-MM fwd+bwd TFLOP/s (% MFMA peak)", "unit": "TFLOP/s", "value": tflops, "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / args.steps, "mm_ms": ms,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32",
+            "data": "synthetic", "pct_mfma_peak": 100.0 * tflops / peak,
+            "config": {"workload": f"{cfg.name}: I={cfg.I}, {len(cfg.layers)} layer call(s), {cfg.Z1}x{cfg.Z2} tiles, "
+                                   f"|M|={cfg.m_size}", "reduce": args.reduce, "dm_workspace": ws is not None},
+            "roofline": {"kernel": "whole step (all MM kernels)", "bound": "mfma" if bf16 else "alu", "achieved": tflops,
+                         "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None}}
 
 
 def main():
@@ -67,6 +127,9 @@ def main():
     roast.load()
     torch.cuda.set_device(0)
     mode = roast.ROAST_REDUCE_ATOMIC if args.reduce == "atomic" else roast.ROAST_REDUCE_DETERMINISTIC
+    if args.workload != "default":
+        print(json.dumps(bench_mm_config(args, roast, wl, torch, np, to_dev, mode)))
+        return
 
     # ------------------------------------------------------------------ inputs (resident before timing)
     mcfg = wl.CONFIGS["cfg2_bert_ffn_bf16"]
@@ -147,8 +210,16 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    per_call = {n: float(np.mean([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)]))
-                for i, n in enumerate(names)}                       # ms, mean over the timed steps
+    samples = {n: np.array([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)])
+               for i, n in enumerate(names)}                        # ms per call, one sample per timed step
+    per_call = {n: float(np.mean(v)) for n, v in samples.items()}
+    # zeroing dM is the caller's job and outside the step; its cost is reported beside it
+    z0, z1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    z0.record()
+    for _ in range(20):
+        dM.zero_()
+    z1.record()
+    torch.cuda.synchronize()
 
     result = {"metric": "ROAST-MM fwd+bwd TFLOP/s (% MFMA peak); ROAST-embedding GB/s (% HBM peak)",
               "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -157,7 +228,10 @@ def main():
               "config": {"workload": "cfg2_bert_ffn_bf16 (ROAST-MM 8192x768x3072 + 8192x3072x768, 64x64 tiles, "
                                      "|M|=47185) + cfg4_dlrm_embed_f32 (1703936 lookups x 128, chunk 32, |M|=1.28M)",
                          "reduce": args.reduce, "dm_workspace": ws is not None},
-              "per_call_ms": per_call}
+              "per_call_ms": per_call,
+              "per_call_median_ms": {n: float(np.median(v)) for n, v in samples.items()},
+              "per_call_min_ms": {n: float(np.min(v)) for n, v in samples.items()},
+              "dM_zero_ms": z0.elapsed_time(z1) / 20}
 
     flop_layer = {"l1": 2.0 * I * l1.H * l1.O, "l2": 2.0 * I * l2.H * l2.O}
     if not args.embed_only:
