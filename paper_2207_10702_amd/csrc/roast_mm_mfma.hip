@@ -4,10 +4,12 @@
 //
 // One workgroup computes a BM x BN = 256 x 128 block of the output with specialised waves: the
 // first NC waves are consumers, each owning a (BM/WGM) x (BN/WGN) sub-block in fp32 accumulators and
-// doing nothing but ds_read_b128 + v_mfma_f32_32x32x16_bf16; the last four waves are producers that
-// bring the next operands into LDS.  Forward / dX run eight consumers (two per SIMD, 64 x 64 each, so
-// that one wave's LDS waits hide behind the other's MFMAs) plus the producers, 168 registers per
-// lane; dM runs four consumers (128 x 64 each) because its producers need more registers.  The
+// doing nothing but ds_read_b128 + v_mfma_f32_32x32x16_bf16; the waves after them are producers that
+// bring the next operands into LDS.  Forward / dX run sixteen waves, 128 registers per lane: eight
+// consumers (two per SIMD, 64 x 64 each, so that one wave's LDS waits hide behind the other's
+// MFMAs), four producers that only issue the direct-to-LDS loads of the activation operand and
+// four that only stage the weight operand.  dM runs four consumers (128 x 64 each) and four
+// producers that stage both operands, because transposing both needs more registers.  The
 // contraction runs in steps of BK = 64 with one workgroup barrier per step.
 //
 // Both operands sit in LDS as [row][k] with 128-byte rows whose 16-byte chunks are XOR-swizzled,
@@ -72,11 +74,6 @@ constexpr int vmcnt_only(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0f70; }
 // Byte offset of 16-byte chunk `chunk` (0..7) of row `row` inside an operand tile.
 __device__ inline int lds_off(int row, int chunk) {
   return row * 128 + (((chunk ^ row ^ (row >> 3)) & 7) << 4);
-}
-
-// Fragment of a 32-row block for k16 sub-step ks: lane -> row (lane & 31), k = 8*(lane >> 5) .. +7.
-__device__ inline bf16x8 frag(const char* tile, int row0, int ks, int lane) {
-  return *reinterpret_cast<const bf16x8*>(tile + lds_off(row0 + (lane & 31), ks * 2 + (lane >> 5)));
 }
 
 struct KernArgs {
@@ -195,9 +192,15 @@ struct RegSet {
 
 
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
-__global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p) {
-  constexpr int NC = WGM * WGN;                  // consumer waves; waves NC .. NC+3 are the producers
-  constexpr int NT = (NC + 4) * 64;              // threads of the workgroup
+__global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void k_roast_mfma(KernArgs p) {
+  constexpr int NC = WGM * WGN;                  // consumer waves
+  // Producer waves follow the consumers.  dM: four, each staging a quarter of both operands.
+  // Forward / dX: eight -- waves NC..NC+3 only issue the direct-to-LDS loads of the activation
+  // operand, waves NC+4..NC+7 only stage the weight operand -- because a wave's vector-memory
+  // instructions were measured to issue more than 100 cycles apart next to busy consumers, so the
+  // loads of a step are spread over twice as many waves.
+  constexpr int NPW = (MODE == MODE_DM) ? 4 : 8;
+  constexpr int NT = (NC + NPW) * 64;            // threads of the workgroup
   static_assert(NC == 4 || NC == 8, "one or two consumer waves per SIMD");
   using Ctx = ProdCtx<MODE, BM, BN>;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;  // consumer wave tile
@@ -275,12 +278,14 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     // sit at the barrier (measured: the two phases then serialise).
     __builtin_amdgcn_s_setprio(3);
     Ctx c;
-    c.ptid = tid - NC * 64;
+    constexpr int B_WAVE0 = NC + (ADMA ? 4 : 0);   // first wave that stages the weight operand
+    const bool a_producer = ADMA && wave < B_WAVE0;
+    c.ptid = a_producer ? 0 : tid - B_WAVE0 * 64;
     const int pt = c.ptid;
     // A operand: producer wave w copies rows w*BM/4 .. +BM/4 of the tile, 8 rows per instruction.
     // A direct-to-LDS load puts lane l's 16 bytes at (LDS base) + 16*l, i.e. row l/8, physical chunk
     // l%8 of that 8-row group -- so the lane fetches the logical chunk the XOR swizzle keeps there.
-    if (ADMA) {
+    if (a_producer) {
 #pragma unroll
       for (int q = 0; q < Ctx::A_LOADS; ++q) {
         const int r = (wave - NC) * (BM / 4) + q * 8 + (lane >> 3);
@@ -438,38 +443,29 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     // direct-to-LDS loads were issued one iteration earlier (after barrier s-2, when the consumers
     // had finished step s-3) and are waited for just before barrier s.
     // Register loads run NSETS steps ahead of their use (one register set per step in flight).
-    // The loop body is branch-free (a step index past the end is clamped and its data never
-    // stored) so that the in-order wait counts can leave the newer loads in flight:
-    //   issue order in iteration s:  A(s+1) [A_LOADS], B(s+NSETS) [B_LOADS]
-    //   A(s) must have landed before barrier s; younger than it are B(s-1+NSETS), A(s+1), B(s+NSETS).
+    // The loop bodies are branch-free (a step index past the end is clamped and its data never
+    // stored) so that the in-order wait counts can leave the newer loads in flight.  The waves that
+    // have direct-to-LDS loads in flight use raw s_barrier instructions behind explicit s_waitcnt
+    // values: the compiler's fence would drain every one of those loads.
     // fp32 weight tiles take twice the registers; twelve waves leave 168 registers per lane
     constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : (NC == 8 ? 3 : 4);
-    constexpr int B_LOADS = MODE == MODE_FWD ? (SHADOW ? 4 : Ctx::FW_BLK * 8)
-                          : (MODE == MODE_DX ? Ctx::DX_LOADS * (SHADOW ? 1 : 2) : 0);
-    static_assert(Ctx::A_LOADS + 2 * B_LOADS < 64, "vmcnt is a 6-bit counter");
-    // The usual barrier (fence + s_barrier) would wait for every outstanding direct-to-LDS load.
-    // What barrier s has to publish is this wave's LDS writes (lgkmcnt 0) and A(s) (the vmcnt
-    // above); the younger loads stay in flight across it.
-    auto barrier_main = [&]() {
-      if constexpr (ADMA) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS + 2 * B_LOADS) & ~0x0f00);
-        __builtin_amdgcn_s_barrier();
-      } else {
-        __syncthreads();
+    if (a_producer) {
+      // iteration s: fetch A(s+1), then wait until A(s) has landed (only A(s+1) is younger)
+      if (nsteps > 0) dma_issue(0);
+      for (int s = 0; s < nsteps; ++s) {
+        dma_issue(s + 1);
+        __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS));
+        __builtin_amdgcn_s_barrier();                    // barrier s
       }
-    };
-    auto barrier_tail = [&]() {         // no register loads are issued any more: only A(s+1) is younger
-      if constexpr (ADMA) {
-        __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS) & ~0x0f00);
-        __builtin_amdgcn_s_barrier();
-      } else {
-        __syncthreads();
-      }
-    };
+      // Nothing may still be on its way to LDS when the consumers start to reuse the stages for
+      // the epilogue (and when the waves end); the barrier pairs with the consumers' one below.
+      __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+      __builtin_amdgcn_s_barrier();
+      return;
+    }
     RegSet<MODE, BM, BN, SHADOW> rs[NSETS];
     const int last = nsteps - 1;
     if (nsteps > 0) {
-      dma_issue(0);
 #pragma unroll
       for (int j = 0; j < NSETS; ++j) load_global(rs[j], min(j, last));
     }
@@ -477,26 +473,19 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     for (; s + NSETS <= nsteps; s += NSETS) {
 #pragma unroll
       for (int j = 0; j < NSETS; ++j) {
-        dma_issue(s + j + 1);
         store_lds(rs[j], s + j);
         load_global(rs[j], min(s + j + NSETS, last));
-        barrier_main();                                  // barrier s + j
+        __syncthreads();                                 // barrier s + j
       }
     }
 #pragma unroll
     for (int j = 0; j < NSETS - 1; ++j) {                // remaining steps (fewer than NSETS)
       if (s + j < nsteps) {
-        dma_issue(s + j + 1);
         store_lds(rs[j], s + j);
-        barrier_tail();
+        __syncthreads();
       }
     }
-    // Nothing may still be on its way to LDS when the consumers start to reuse the stages for
-    // the epilogue (and when the waves end); the barrier pairs with the consumers' one below.
-    if constexpr (ADMA) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
-      __builtin_amdgcn_s_barrier();
-    }
+    if constexpr (ADMA) __syncthreads();                 // pairs with the consumers' barrier before the epilogue
     return;
   }
 
@@ -510,6 +499,21 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+  // Fragment addresses.  Row r0 + 32*i + (lane & 31), 16-byte chunk 2*ks + (lane >> 5): the swizzle
+  // term (row ^ row >> 3) & 7 only depends on the lane and on the parity of i (32 rows flip bit 2 of
+  // row >> 3, 64 rows change nothing), and 2*ks enters the chunk index by XOR -- so one offset per
+  // lane and parity serves every fragment as (offset ^ ks << 5) + 8192 * (i >> 1), and no table of
+  // precomputed addresses competes with the accumulators for registers.
+  uint32_t a_lane[2] = {(uint32_t)lds_off(wm * WTM + (lane & 31), lane >> 5),
+                        (uint32_t)lds_off(wm * WTM + 32 + (lane & 31), lane >> 5)};
+  uint32_t b_lane[2] = {(uint32_t)lds_off(wn * WTN + (lane & 31), lane >> 5),
+                        (uint32_t)lds_off(wn * WTN + 32 + (lane & 31), lane >> 5)};
+  auto afrag = [&](const char* At, int i, int ks) {
+    return *reinterpret_cast<const bf16x8*>(At + ((a_lane[i & 1] ^ (uint32_t)(ks << 5)) + (uint32_t)((i >> 1) * 8192)));
+  };
+  auto bfrag = [&](const char* Bt, int j, int ks) {
+    return *reinterpret_cast<const bf16x8*>(Bt + ((b_lane[j & 1] ^ (uint32_t)(ks << 5)) + (uint32_t)((j >> 1) * 8192)));
+  };
   // FWD / DX issue the MFMA with the operands swapped (weight fragment first), so that a lane ends
   // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
   // Fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued.
@@ -517,12 +521,15 @@ __global__ __launch_bounds__((WGM * WGN + 4) * 64) void k_roast_mfma(KernArgs p)
     __syncthreads();                                     // barrier s: stages hold step s
     const char* At = a_stage(s);
     const char* Bt = b_stage(s);
+    // (opaque to the optimiser, so that the per-fragment addresses are formed in the loop from these
+    // four values instead of being kept in two dozen registers across it)
+    asm volatile("" : "+v"(a_lane[0]), "+v"(a_lane[1]), "+v"(b_lane[0]), "+v"(b_lane[1]));
     bf16x8 af[2][MI], bfr[2][NI];
     auto fetch = [&](int ks, int buf) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i) af[buf][i] = frag(At, wm * WTM + i * 32, ks, lane);
+      for (int i = 0; i < MI; ++i) af[buf][i] = afrag(At, i, ks);
 #pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[buf][j] = frag(Bt, wn * WTN + j * 32, ks, lane);
+      for (int j = 0; j < NI; ++j) bfr[buf][j] = bfrag(Bt, j, ks);
     };
     fetch(0, 0);
 #pragma unroll
@@ -618,7 +625,7 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + 4) * 64), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64), smem, s, p);
   return hip_status(hipGetLastError());
 }
 
