@@ -32,6 +32,8 @@
 // forward / dX goes through LDS (the operand stages, free by then) so that global stores are 16
 // bytes per lane and row-contiguous.  Workgroups are numbered so that each XCD's L2 serves a
 // contiguous band of output row blocks.
+#include <type_traits>
+
 #include "roast_internal.hpp"
 
 namespace roast {
@@ -186,20 +188,18 @@ struct RegSet {
   // ... or from its bf16 shadow
   uint4v fs_reg[(MODE == MODE_FWD && SHADOW) ? 4 : 1];
   uint4v ds_reg[(MODE == MODE_DX && SHADOW) ? Ctx::DX_LOADS : 1];
-  TLoad<MODE == MODE_DM ? BM : 128> ta;
-  TLoad<MODE == MODE_DM ? BN : 128> tb;
 };
 
 
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
-__global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void k_roast_mfma(KernArgs p) {
+__global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p) {
   constexpr int NC = WGM * WGN;                  // consumer waves
-  // Producer waves follow the consumers.  dM: four, each staging a quarter of both operands.
-  // Forward / dX: eight -- waves NC..NC+3 only issue the direct-to-LDS loads of the activation
-  // operand, waves NC+4..NC+7 only stage the weight operand -- because a wave's vector-memory
-  // instructions were measured to issue more than 100 cycles apart next to busy consumers, so the
-  // loads of a step are spread over twice as many waves.
-  constexpr int NPW = (MODE == MODE_DM) ? 4 : 8;
+  // Eight producer waves follow the consumers: waves NC..NC+3 bring in the A operand (forward / dX:
+  // direct-to-LDS loads of the activations; dM: X transposed through registers), waves NC+4..NC+7
+  // the B operand (weight tile; dM: dY transposed).  A wave's vector-memory instructions were
+  // measured to issue more than 100 cycles apart next to busy consumers, so the loads of a step are
+  // spread over eight waves rather than four.
+  constexpr int NPW = 8;
   constexpr int NT = (NC + NPW) * 64;            // threads of the workgroup
   static_assert(NC == 4 || NC == 8, "one or two consumer waves per SIMD");
   using Ctx = ProdCtx<MODE, BM, BN>;
@@ -278,9 +278,10 @@ __global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void 
     // sit at the barrier (measured: the two phases then serialise).
     __builtin_amdgcn_s_setprio(3);
     Ctx c;
-    constexpr int B_WAVE0 = NC + (ADMA ? 4 : 0);   // first wave that stages the weight operand
-    const bool a_producer = ADMA && wave < B_WAVE0;
-    c.ptid = a_producer ? 0 : tid - B_WAVE0 * 64;
+    constexpr int B_WAVE0 = NC + 4;                // first wave that stages the B operand
+    const bool a_role = wave < B_WAVE0;
+    const bool a_producer = ADMA && a_role;        // issues direct-to-LDS loads only
+    c.ptid = a_role ? tid - NC * 64 : tid - B_WAVE0 * 64;
     const int pt = c.ptid;
     // A operand: producer wave w copies rows w*BM/4 .. +BM/4 of the tile, 8 rows per instruction.
     // A direct-to-LDS load puts lane l's 16 bytes at (LDS base) + 16*l, i.e. row l/8, physical chunk
@@ -380,17 +381,11 @@ __global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void 
           r.dx_reg[2 * q + 1] = floatx4{m1v.v[0], m1v.v[1], m1v.v[2], m1v.v[3]};
           r.dx_sgn[q] = s_sgn[e];
         }
-      } else if (MODE == MODE_DM) {
-        r.ta.load(p.A, p.lda, k0, I - 1, c.ta_col, pt >> 5);
-        __builtin_amdgcn_sched_barrier(0);
-        r.tb.load(p.B, p.ldb, k0, I - 1, c.tb_col, pt >> 5);
       }
       __builtin_amdgcn_sched_barrier(0);
     };
 
     auto store_lds = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
-      const int k0 = k_begin + step * BK;
-      char* At = a_stage(step);
       char* Bt = b_stage(step);
       if (MODE == MODE_FWD && SHADOW) {
         // flipping the sign bit of a bf16 equals rounding the negated fp32 value
@@ -431,9 +426,6 @@ __global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void 
                       pack_bf16x2(v[0] * sg, v[1] * sg), pack_bf16x2(v[2] * sg, v[3] * sg)};
           *reinterpret_cast<uint4v*>(Bt + lds_off((pt >> 3) + 32 * q, pt & 7)) = o;
         }
-      } else if (MODE == MODE_DM) {
-        r.ta.store(At, k0, k_end, pt & 31, pt >> 5);
-        r.tb.store(Bt, k0, k_end, pt & 31, pt >> 5);
       }
     };
 
@@ -447,8 +439,43 @@ __global__ __launch_bounds__((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64) void 
     // stored) so that the in-order wait counts can leave the newer loads in flight.  The waves that
     // have direct-to-LDS loads in flight use raw s_barrier instructions behind explicit s_waitcnt
     // values: the compiler's fence would drain every one of those loads.
-    // fp32 weight tiles take twice the registers; twelve waves leave 168 registers per lane
+    // fp32 weight tiles take twice the registers; sixteen waves leave 128 registers per lane
     constexpr int NSETS = (MODE != MODE_DM && !SHADOW) ? 2 : (NC == 8 ? 3 : 4);
+    if constexpr (MODE == MODE_DM) {
+      // Each role has its own loop, so that only its own transposing register sets exist.
+      auto dm_loop = [&](auto* loader_type, const uint16_t* src, int64_t ld, int col, bool is_a) {
+        using TL = typename std::remove_pointer<decltype(loader_type)>::type;
+        TL rs[NSETS];
+        auto fetch = [&](TL& r, int step) { r.load(src, ld, k_begin + step * BK, I - 1, col, pt >> 5); };
+        auto stage = [&](TL& r, int step) {
+          r.store(is_a ? a_stage(step) : b_stage(step), k_begin + step * BK, k_end, pt & 31, pt >> 5);
+        };
+        const int last = nsteps - 1;
+        if (nsteps > 0) {
+#pragma unroll
+          for (int j = 0; j < NSETS; ++j) fetch(rs[j], min(j, last));
+        }
+        int s = 0;
+        for (; s + NSETS <= nsteps; s += NSETS) {
+#pragma unroll
+          for (int j = 0; j < NSETS; ++j) {
+            stage(rs[j], s + j);
+            fetch(rs[j], min(s + j + NSETS, last));
+            __syncthreads();                             // barrier s + j
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < NSETS - 1; ++j) {
+          if (s + j < nsteps) {
+            stage(rs[j], s + j);
+            __syncthreads();
+          }
+        }
+      };
+      if (a_role) dm_loop((TLoad<BM>*)nullptr, p.A, p.lda, c.ta_col, true);
+      else dm_loop((TLoad<BN>*)nullptr, p.B, p.ldb, c.tb_col, false);
+      return;
+    }
     if (a_producer) {
       // iteration s: fetch A(s+1), then wait until A(s) has landed (only A(s+1) is younger)
       if (nsteps > 0) dma_issue(0);
@@ -625,7 +652,7 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + (MODE == MODE_DM ? 4 : 8)) * 64), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + 8) * 64), smem, s, p);
   return hip_status(hipGetLastError());
 }
 
@@ -703,7 +730,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.B = (const uint16_t*)dY; p.ldb = ldy; p.dM = dM; p.G = Gws;
   p.rows_per_split = (int)rows;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
-  return launch<MODE_DM, BM, BN, 2, 2, false>(p, grid, s);
+  return launch<MODE_DM, BM, BN, 4, 2, false>(p, grid, s);
 }
 
 }  // namespace roast
