@@ -152,6 +152,9 @@ MFMA_SHAPES = [
     (256, 192, 96, 64, 32, 9000),
     (1000, 64, 576, 64, 64, 4096),
     (700, 640, 64, 64, 64, 5000),
+    (300, 128, 240, 64, 12, 20000),     # forward on the MFMA path, but tiles too narrow for the 8-column shadow reads
+    (520, 192, 136, 64, 8, 7000),       # 17 hash tiles under one 128-column block; ragged last block
+    (257, 64, 128, 64, 128, 8193),      # one row past a 256-row block; |M| = one tile + 1: two offsets only
 ]
 
 
