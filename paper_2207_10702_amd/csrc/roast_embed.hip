@@ -75,6 +75,30 @@ __global__ __launch_bounds__(256) void k_embed(EmbedArgs a, int lpi_log2, int wa
   const int which = lane >> lpi_log2; // which chunk of the step I serve
   const int n_here = rows_here * C;
   const int64_t g0 = n0 * C;
+  if constexpr (VEC == 4 && !BWD) {
+    // Forward, full chunks: the gathered reads of M are latency-bound (L2 / memory-side cache), so
+    // each wave keeps U chunks per lane group in flight before it stores any of them.
+    constexpr int U = 4;
+    if (lpi * 4 == a.Z) {          // one 16-byte piece per lane and chunk (Z <= 256): the common case
+      for (int j0 = 0; j0 < n_here; j0 += U * items_per_step) {
+        vfloat4 v[U];
+        int64_t ob[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int j = min(j0 + u * items_per_step + which, n_here - 1);
+          const uint32_t key = keys[j];
+          const float scale = (key & 0x80000000u) ? -a.lambda : a.lambda;
+          const f4u m = *reinterpret_cast<const f4u*>(M + (key & 0x7fffffffu) + sub * 4);
+          v[u] = vfloat4{scale * m.v[0], scale * m.v[1], scale * m.v[2], scale * m.v[3]};
+          ob[u] = (g0 + j) * a.Z + sub * 4;      // D % Z == 0: chunk g starts at g*Z in the dense output
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+          if (j0 + u * items_per_step + which < n_here) __builtin_nontemporal_store(v[u], reinterpret_cast<vfloat4*>(out + ob[u]));
+      }
+      return;
+    }
+  }
   for (int j0 = 0; j0 < n_here; j0 += items_per_step) {
     const int j = j0 + which;
     if (j >= n_here) continue;
@@ -168,9 +192,9 @@ roast_status launch_embed(const EmbedArgs& a, const int64_t* rows, const uint32_
 // Bucketed gradient: fp32 global atomics top out near 0.3 T adds/s on this chip, an order of
 // magnitude short of what streaming dOut needs, so the scatter-add is reorganised by destination.
 //   1. route:  every lookup is hashed once; each of its chunks is appended to the list of the bucket
-//              (R consecutive slots of M) its offset falls in.  A workgroup sorts its chunks by
-//              bucket in LDS, reserves list space with one global add per bucket, and copies the
-//              sorted entries out in runs.  Lists have a fixed capacity; a chunk that does not fit
+//              (R consecutive slots of M) its offset falls in.  A workgroup ranks its chunks inside
+//              each bucket with LDS counters, reserves list space with one global add per bucket,
+//              and writes every entry to reserved base + rank.  Lists have a fixed capacity; a chunk that does not fit
 //              is added straight into dM with global atomics instead (rare: only under extreme skew).
 //   2. accum:  one workgroup per (bucket, list segment) zeroes an fp64 LDS image of its R (+Z)
 //              slots, adds its chunks of dOut into it with LDS atomics, and flushes the image to dM
@@ -297,12 +321,10 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
   const int C = (int)a.C;
   const int rows_wg = kRouteItems / C;
   constexpr int items = kRouteItems;
-  uint2* sorted = reinterpret_cast<uint2*>(s_route);              // [items] entries ordered by bucket
-  uint32_t* s_key = s_route + 2 * items;                           // [items]
+  uint32_t* s_key = s_route;                                       // [items]
   uint16_t* s_pos = reinterpret_cast<uint16_t*>(s_key + items);   // [items] rank inside (workgroup, bucket)
   uint32_t* hist = s_key + items + items / 2;                      // [nb]  chunks of this workgroup per bucket
-  uint32_t* lstart = hist + nb;             // [nb]  start of the bucket's run in the sorted array
-  uint32_t* gbase = lstart + nb;            // [nb]  reserved position in the bucket's global list
+  uint32_t* gbase = hist + nb;                                     // [nb]  reserved position in the bucket's global list
   for (int i = threadIdx.x; i < nb; i += 256) hist[i] = 0u;
   __syncthreads();
   const int64_t n0 = (int64_t)blockIdx.x * rows_wg;
@@ -315,53 +337,17 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
     });
   }
   __syncthreads();
-  // exclusive scan of hist -> lstart (nb <= 2048: 8 entries per thread, then a scan over 256 partials)
-  __shared__ uint32_t part[256];
-  {
-    const int per = (nb + 255) / 256;
-    uint32_t sum = 0;
-    for (int k = 0; k < per; ++k) {
-      const int i = threadIdx.x * per + k;
-      if (i < nb) sum += hist[i];
-    }
-    // exclusive scan of the 256 per-thread sums: inclusive scan inside each wave by shuffles, then
-    // the four wave totals
-    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    uint32_t inc = sum;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-      const uint32_t up = (uint32_t)__shfl_up((int)inc, d, 64);
-      if (lane >= d) inc += up;
-    }
-    if (lane == 63) part[wv] = inc;
-    __syncthreads();
-    uint32_t wave_base = 0;
-    for (int w = 0; w < wv; ++w) wave_base += part[w];
-    __syncthreads();
-    part[threadIdx.x] = wave_base + inc - sum;
-    __syncthreads();
-    uint32_t acc = part[threadIdx.x];
-    for (int k = 0; k < per; ++k) {
-      const int i = threadIdx.x * per + k;
-      if (i < nb) {
-        lstart[i] = acc;
-        acc += hist[i];
-        gbase[i] = hist[i] ? atomicAdd(&cursor[i], hist[i]) : 0u;
-      }
-    }
-  }
+  // one global add per (workgroup, bucket) reserves that many consecutive list slots
+  for (int i = threadIdx.x; i < nb; i += 256) gbase[i] = hist[i] ? atomicAdd(&cursor[i], hist[i]) : 0u;
   __syncthreads();
+  // every chunk knows its bucket and its rank inside (workgroup, bucket): that is its list slot.
+  // The entries of one run land next to each other, L2 merges them into whole lines.
   const int n_here = rows_here * C;
   for (int i = threadIdx.x; i < n_here; i += 256) {
     const uint32_t key = s_key[i];
     const uint32_t b = (key & 0x7fffffffu) >> r_log2;
-    sorted[lstart[b] + s_pos[i]] = make_uint2((uint32_t)(n0 * C + i), key);
-  }
-  __syncthreads();
-  for (int i = threadIdx.x; i < n_here; i += 256) {
-    const uint2 e = sorted[i];
-    const uint32_t b = (e.y & 0x7fffffffu) >> r_log2;
-    const uint32_t pos = gbase[b] + ((uint32_t)i - lstart[b]);
+    const uint32_t pos = gbase[b] + s_pos[i];
+    const uint2 e = make_uint2((uint32_t)(n0 * C + i), key);
     if (pos < cap) {
       list[(size_t)b * cap + pos] = e;
     } else {
@@ -481,7 +467,7 @@ roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* 
   uint2* list = (uint2*)(base + p.list_off);
   hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, (int64_t)p.nb);
   const int rows_wg = kRouteItems / (int)a.C;
-  const size_t lds_route = (size_t)kRouteItems * (8 + 4 + 2) + (size_t)3 * p.nb * 4;
+  const size_t lds_route = (size_t)kRouteItems * (4 + 2) + (size_t)2 * p.nb * 4;
   static bool configured = false;   // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
