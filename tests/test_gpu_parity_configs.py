@@ -88,10 +88,14 @@ def test_cfg2_bert_ffn_bf16_full_size(roast):
     d1 = roast.mm_desc(l1.H, l1.O, cfg.Z1, cfg.Z2, cfg.m_size, l1.layer_id, cfg.lam, h)
     d2 = roast.mm_desc(l2.H, l2.O, cfg.Z1, cfg.Z2, cfg.m_size, l2.layer_id, cfg.lam, h)
     Md, Xd, dYd = to_dev(inp.M), to_dev(inp.X[l1.name]), to_dev(inp.dY[l2.name])
-    H1 = roast.roast_mm_fwd(d1, Xd, Md)
-    Y = roast.roast_mm_fwd(d2, H1, Md)
-    dH1 = roast.roast_mm_bwd_dx(d2, dYd, Md)
-    dX = roast.roast_mm_bwd_dx(d1, dH1, Md)
+    # the launch configuration bench.py times: weights read from the bf16 shadow of M, dM without workspace
+    Mb = roast.roast_m_shadow_bf16(Md)
+    H1 = roast.roast_mm_fwd(d1, Xd, Md, M_bf16=Mb)
+    Y = roast.roast_mm_fwd(d2, H1, Md, M_bf16=Mb)
+    dH1 = roast.roast_mm_bwd_dx(d2, dYd, Md, M_bf16=Mb)
+    dX = roast.roast_mm_bwd_dx(d1, dH1, Md, M_bf16=Mb)
+    # ... and the shadow must not change a bit
+    assert torch.equal(H1, roast.roast_mm_fwd(d1, Xd, Md)) and torch.equal(dX, roast.roast_mm_bwd_dx(d1, dH1, Md))
     dM2 = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
     dM1 = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
     roast.roast_mm_bwd_dM(d2, H1, dYd, dM2)
@@ -129,6 +133,7 @@ def test_cfg3_bert_stack_bf16_full_size(roast):
     rng = np.random.default_rng(3)
     h, lam = inp.hash, float(np.float32(cfg.lam))
     Md = to_dev(inp.M)
+    Mb = roast.roast_m_shadow_bf16(Md)
     dev = {}
     for l in cfg.layers[:4]:          # one X / dY per distinct shape, shared by the 12 transformer layers
         dev[(l.H, l.O)] = (to_dev(inp.X[l.name]), to_dev(inp.dY[l.name]))
@@ -138,8 +143,8 @@ def test_cfg3_bert_stack_bf16_full_size(roast):
     for idx, l in enumerate(cfg.layers):
         d = roast.mm_desc(l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size, l.layer_id, cfg.lam, h)
         Xd, dYd = dev[(l.H, l.O)]
-        Y = roast.roast_mm_fwd(d, Xd, Md)
-        dX = roast.roast_mm_bwd_dx(d, dYd, Md)
+        Y = roast.roast_mm_fwd(d, Xd, Md, M_bf16=Mb)
+        dX = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=Mb)
         roast.roast_mm_bwd_dM(d, Xd, dYd, dM)
         off, sgn = roast.roast_tile_index_device(d)
         eoff, esgn = oracle.tile_index(h, l.layer_id, l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size)
@@ -216,8 +221,9 @@ def test_cfg5_large_bf16_full_size(roast):
     h, lam = inp.hash, float(np.float32(cfg.lam))
     d = roast.mm_desc(l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size, l.layer_id, cfg.lam, h)
     Md, Xd, dYd = to_dev(inp.M), to_dev(inp.X[l.name]), to_dev(inp.dY[l.name])
-    Y = roast.roast_mm_fwd(d, Xd, Md)
-    dX = roast.roast_mm_bwd_dx(d, dYd, Md)
+    Mb = roast.roast_m_shadow_bf16(Md)
+    Y = roast.roast_mm_fwd(d, Xd, Md, M_bf16=Mb)
+    dX = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=Mb)
     dM = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
     roast.roast_mm_bwd_dM(d, Xd, dYd, dM)
     torch.cuda.synchronize()
