@@ -544,24 +544,36 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   // FWD / DX issue the MFMA with the operands swapped (weight fragment first), so that a lane ends
   // up with 4 consecutive output columns of one output row -- what the coalesced epilogue needs.
   // Fragments of sub-step ks+1 are requested before the MFMAs of sub-step ks are issued.
+  // The loop is rotated by a quarter step: barrier s+1 sits before the last sub-step of step s, when
+  // every fragment of step s is already in registers, and the first fragments of step s+1 are
+  // requested right behind it -- the MFMAs of two sub-steps are queued while a wave waits at the
+  // barrier, and no LDS latency is exposed after it.  (Reading step s is over before barrier s+1, so
+  // the producers' rule "a stage may be refilled once the barrier after its step is passed" holds.)
+  bf16x8 af[2][MI], bfr[2][NI];
+  auto fetch = [&](int step, int ks, int buf) {
+    const char* At = a_stage(step);
+    const char* Bt = b_stage(step);
+#pragma unroll
+    for (int i = 0; i < MI; ++i) af[buf][i] = afrag(At, i, ks);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) bfr[buf][j] = bfrag(Bt, j, ks);
+  };
+  if (nsteps > 0) {
+    __syncthreads();                                     // barrier 0: stages hold step 0
+    fetch(0, 0, 0);
+  }
   for (int s = 0; s < nsteps; ++s) {
-    __syncthreads();                                     // barrier s: stages hold step s
-    const char* At = a_stage(s);
-    const char* Bt = b_stage(s);
     // (opaque to the optimiser, so that the per-fragment addresses are formed in the loop from these
     // four values instead of being kept in two dozen registers across it)
     asm volatile("" : "+v"(a_lane[0]), "+v"(a_lane[1]), "+v"(b_lane[0]), "+v"(b_lane[1]));
-    bf16x8 af[2][MI], bfr[2][NI];
-    auto fetch = [&](int ks, int buf) {
-#pragma unroll
-      for (int i = 0; i < MI; ++i) af[buf][i] = afrag(At, i, ks);
-#pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[buf][j] = bfrag(Bt, j, ks);
-    };
-    fetch(0, 0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      if (ks + 1 < BK / 16) fetch(ks + 1, (ks + 1) & 1);
+      if (ks + 1 < BK / 16) {
+        fetch(s, ks + 1, (ks + 1) & 1);
+      } else if (s + 1 < nsteps) {
+        __syncthreads();                                 // barrier s+1: stages hold step s+1
+        fetch(s + 1, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
