@@ -276,7 +276,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     // The producers' instructions are few but on the critical path of every step; with equal
     // priority the SIMD's arbiter favours the consumer waves and the producer only runs while they
     // sit at the barrier (measured: the two phases then serialise).
-    __builtin_amdgcn_s_setprio(3);
+    // The waves that only issue direct-to-LDS loads have nothing on the critical path but the wait
+    // for their loads: they stay at the default priority (raising it too cost 4-8 %).
+    if (!(MODE != MODE_DM && wave < NC + 4)) __builtin_amdgcn_s_setprio(3);
     Ctx c;
     constexpr int B_WAVE0 = NC + 4;                // first wave that stages the B operand
     const bool a_role = wave < B_WAVE0;
