@@ -22,3 +22,4 @@ from .roast_oracle import (  # noqa: F401
     embed_bwd,
     num_threads,
 )
+from . import optim_oracle as optim  # noqa: F401,E402
