@@ -56,6 +56,35 @@ def parse():
     return p.parse_args()
 
 
+def time_optimizer(roast, torch, M, dM, Mb):
+    def timed(fn, reps=20):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    big_n = 64 << 20
+    big = [torch.zeros(big_n, dtype=torch.float32, device="cuda") for _ in range(4)]
+    big_b = torch.empty(roast.roast_m_shadow_bytes(big_n) // 2, dtype=torch.bfloat16, device="cuda")
+    small = [torch.zeros_like(M) for _ in range(2)]
+    Mc, dMc = M.clone(), dM.clone()
+    # bytes per parameter: M read+write, dM read+write (cleared), states read+write, shadow 2 x 2 written
+    per_param = {"sgd": 4 * 4 + 4, "adagrad": 6 * 4 + 4, "adam": 8 * 4 + 4}
+    for name, kind in (("sgd", roast.ROAST_OPT_SGD), ("adagrad", roast.ROAST_OPT_ADAGRAD), ("adam", roast.ROAST_OPT_ADAM)):
+        d = roast.optim_desc(kind, 1e-3, step=3, eps=1e-8)
+        ms_small = timed(lambda: roast.roast_optim_step(d, Mc, dMc, small[0], small[1], Mb))
+        ms_big = timed(lambda: roast.roast_optim_step(d, big[0], big[1], big[2], big[3], big_b), reps=5)
+        out[name] = {"cfg2_M_ms": ms_small, "M_64Mi_ms": ms_big,
+                     "M_64Mi_GBs": per_param[name] * big_n / (ms_big * 1e-3) / 1e9}
+    return out
+
+
 def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     """Forward, dX and dM of every layer of one ROAST-MM configuration, all layers sharing M and dM."""
     cfg = wl.CONFIGS[args.workload]
@@ -232,6 +261,11 @@ def main():
               "per_call_median_ms": {n: float(np.median(v)) for n, v in samples.items()},
               "per_call_min_ms": {n: float(np.min(v)) for n, v in samples.items()},
               "dM_zero_ms": z0.elapsed_time(z1) / 20}
+
+    # The weight update of a training step (outside `value`): one fused pass that applies the rule,
+    # clears dM and refreshes the bf16 shadow.  Timed on config 2's M and on a 64 Mi-entry M (config 5's).
+    if not args.embed_only:
+        result["optimizer"] = time_optimizer(roast, torch, M, dM, Mb)
 
     flop_layer = {"l1": 2.0 * I * l1.H * l1.O, "l2": 2.0 * I * l2.H * l2.O}
     if not args.embed_only:

@@ -192,6 +192,38 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
                              const uint32_t* table_ids, const float* dOut, float* dM,
                              roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Optimizer step on the shared array: the "update weights" leg of the paper's training workload
+ * (training-time tables of the appendix: SGD, Adagrad, Adam on the |M|-sized parameter).  The paper
+ * defines no update rule of its own; these are the textbook rules in the form of the stock optimizers:
+ *   g = dM + weight_decay * M
+ *   SGD     : M -= lr * g
+ *   ADAGRAD : state1 += g*g ;  M -= lr * g / (sqrt(state1) + eps)
+ *   ADAM    : state1 = beta1*state1 + (1-beta1)*g ;  state2 = beta2*state2 + (1-beta2)*g*g ;
+ *             M -= lr * (state1 / (1 - beta1^step)) / (sqrt(state2 / (1 - beta2^step)) + eps)
+ * `step` is the 1-based count of this update (Adam only).  zero_grad != 0 clears dM in the same pass.
+ */
+typedef enum { ROAST_OPT_SGD = 0, ROAST_OPT_ADAGRAD = 1, ROAST_OPT_ADAM = 2 } roast_optimizer;
+
+typedef struct {
+  roast_optimizer kind;
+  float lr, weight_decay;
+  float beta1, beta2, eps;
+  int64_t step;
+  uint32_t zero_grad;
+} roast_optim_desc;
+
+/*
+ * One pass over m_size parameters.  M, dM: m_size fp32, both updated in place (dM only when
+ * zero_grad).  state1: m_size fp32 for ADAGRAD and ADAM, state2: m_size fp32 for ADAM (the caller
+ * zeroes them before the first step); ignored (may be NULL) otherwise.  M_bf16: NULL, or a shadow
+ * buffer as for roast_m_shadow_bf16, refreshed from the new M in the same pass.
+ * All pointers are DEVICE pointers, 16-byte aligned.  ROAST_ERR_ARG: null M / dM / needed state,
+ * misaligned pointer, bad kind, step < 1 for ADAM, beta outside [0, 1).
+ */
+roast_status roast_optim_step(const roast_optim_desc* d, int64_t m_size, float* M, float* dM, float* state1,
+                              float* state2, void* M_bf16, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

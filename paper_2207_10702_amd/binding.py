@@ -18,7 +18,7 @@ ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
            "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
-           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd"]
+           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd", "roast_optim_step"]
 
 
 class RoastError(RuntimeError):
@@ -43,6 +43,13 @@ class RoastEmbedDesc(C.Structure):
     _fields_ = [("D", C.c_int64), ("Z", C.c_int32), ("m_size", C.c_int64), ("lam", C.c_float),
                 ("hash", RoastHash)]
 
+
+class RoastOptimDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("weight_decay", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_int64), ("zero_grad", C.c_uint32)]
+
+
+ROAST_OPT_SGD, ROAST_OPT_ADAGRAD, ROAST_OPT_ADAM = 0, 1, 2
 
 _lib = None
 
@@ -76,6 +83,7 @@ def load() -> C.CDLL:
     lib.roast_embed_bwd_workspace.argtypes = [EP, i64, i32]
     lib.roast_embed_bwd_workspace.restype = sz
     lib.roast_embed_bwd.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.roast_optim_step.argtypes = [C.POINTER(RoastOptimDesc), i64, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
         f = getattr(lib, name)
         if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
@@ -282,3 +290,25 @@ def roast_embed_bwd(desc: RoastEmbedDesc, rows, table_ids, dOut, dM, mode: int =
                                   _vec(dM, torch.float32, "dM"), int(mode), wp, wb, _stream(stream)),
            "roast_embed_bwd")
     return dM
+
+
+def optim_desc(kind: int, lr: float, weight_decay: float = 0.0, beta1: float = 0.9, beta2: float = 0.999,
+               eps: float = 1e-8, step: int = 1, zero_grad: bool = True) -> RoastOptimDesc:
+    return RoastOptimDesc(int(kind), float(lr), float(weight_decay), float(beta1), float(beta2), float(eps),
+                          int(step), 1 if zero_grad else 0)
+
+
+def roast_optim_step(desc: RoastOptimDesc, M, dM, state1=None, state2=None, M_bf16=None, stream=None):
+    """One optimizer step on M (in place); clears dM when desc.zero_grad; refreshes M_bf16 when given."""
+    torch = _torch()
+    n = M.numel()
+    if dM.numel() != n:
+        raise ValueError("dM must have as many entries as M")
+    ptr = lambda t, what: 0 if t is None else _vec(t, torch.float32, what)
+    for t, what in ((state1, "state1"), (state2, "state2")):
+        if t is not None and t.numel() != n:
+            raise ValueError(f"{what} must have as many entries as M")
+    _check(load().roast_optim_step(C.byref(desc), n, _vec(M, torch.float32, "M"), _vec(dM, torch.float32, "dM"),
+                                   ptr(state1, "state1"), ptr(state2, "state2"), _shadow_ptr(M, M_bf16),
+                                   _stream(stream)), "roast_optim_step")
+    return M

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libroast_hip.so")
-SOURCES = ["roast_api.hip", "roast_mm_generic.hip", "roast_mm_mfma.hip", "roast_reduce.hip", "roast_embed.hip"]
+SOURCES = ["roast_api.hip", "roast_mm_generic.hip", "roast_mm_mfma.hip", "roast_reduce.hip", "roast_embed.hip", "roast_optim.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -209,4 +209,20 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
   return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, ws, ws_bytes, (hipStream_t)stream);
 }
 
+roast_status roast_optim_step(const roast_optim_desc* d, int64_t m_size, float* M, float* dM, float* state1,
+                              float* state2, void* M_bf16, void* stream) {
+  if (!d || m_size < 0) return ROAST_ERR_ARG;
+  if (d->kind != ROAST_OPT_SGD && d->kind != ROAST_OPT_ADAGRAD && d->kind != ROAST_OPT_ADAM) return ROAST_ERR_ARG;
+  if (d->kind == ROAST_OPT_ADAM &&
+      (d->step < 1 || !(d->beta1 >= 0.f && d->beta1 < 1.f) || !(d->beta2 >= 0.f && d->beta2 < 1.f)))
+    return ROAST_ERR_ARG;
+  if (m_size == 0) return ROAST_OK;
+  auto bad = [](const void* p) { return p == nullptr || ((uintptr_t)p & 15) != 0; };
+  if (bad(M) || bad(dM)) return ROAST_ERR_ARG;
+  if (d->kind != ROAST_OPT_SGD && bad(state1)) return ROAST_ERR_ARG;
+  if (d->kind == ROAST_OPT_ADAM && bad(state2)) return ROAST_ERR_ARG;
+  if (M_bf16 && ((uintptr_t)M_bf16 & 15) != 0) return ROAST_ERR_ARG;
+  return optim_launch(*d, m_size, M, dM, state1, state2, M_bf16, (hipStream_t)stream);
+}
+
 }  // extern "C"

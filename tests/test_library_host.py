@@ -82,3 +82,21 @@ def test_argument_validation_returns_status_codes_without_touching_the_gpu():
     assert ei.value.status == 3 and "fit" in str(ei.value)
     assert lib.roast_mm_bwd_dM_workspace(C.byref(ok), 128, 0) == 0
     assert lib.roast_mm_bwd_dM_workspace(C.byref(ok), 128, 1) > 64 * 64 * 4
+
+
+def test_optim_step_argument_validation():
+    """Host-side checks of roast_optim_step (no launch happens for any of these)."""
+    import ctypes as C
+
+    from paper_2207_10702_amd import binding as roast
+    lib = roast.load()
+    d = roast.optim_desc(roast.ROAST_OPT_ADAM, 1e-3, step=0)
+    assert lib.roast_optim_step(C.byref(d), 16, 16, 16, 16, 16, None, None) == 1      # step < 1
+    d = roast.optim_desc(7, 1e-3)
+    assert lib.roast_optim_step(C.byref(d), 16, 16, 16, None, None, None, None) == 1  # bad kind
+    d = roast.optim_desc(roast.ROAST_OPT_SGD, 1e-3)
+    assert lib.roast_optim_step(C.byref(d), 16, None, 16, None, None, None, None) == 1   # null M
+    assert lib.roast_optim_step(C.byref(d), 16, 20, 16, None, None, None, None) == 1     # misaligned M
+    assert lib.roast_optim_step(C.byref(d), 0, None, None, None, None, None, None) == 0  # empty: no-op
+    d = roast.optim_desc(roast.ROAST_OPT_ADAGRAD, 1e-3)
+    assert lib.roast_optim_step(C.byref(d), 16, 16, 16, None, None, None, None) == 1     # state1 missing
