@@ -148,6 +148,26 @@ roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, con
 roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
                              const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream);
 
+/*
+ * Small-batch variants of the two products above (Section 3.2's blocked product; the paper's
+ * square-weight timings use batch 512).  With few rows the output has too few tiles to fill the
+ * chip, so the contraction axis is split over workgroups: each writes an fp32 partial output to
+ * the workspace and a second pass sums the parts in a fixed order and rounds once to `dt`.
+ * The *_workspace queries return the bytes that help for these sizes (0: the plain call is used,
+ * e.g. fp32, large I, or a shape the bf16 kernels do not cover).
+ * workspace: NULL (same as the plain call), or a DEVICE buffer, 16-byte aligned, of at least the
+ * queried size (else ROAST_ERR_WORKSPACE); its contents are scratch, owned by the caller, and may be
+ * reused by the next call on the same stream.  Results are deterministic for a fixed shape.
+ */
+size_t roast_mm_fwd_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I);
+size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I);
+roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                             const float* M, const void* M_bf16, void* Y, int64_t ldy, void* workspace,
+                             size_t workspace_bytes, void* stream);
+roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
+                                const float* M, const void* M_bf16, void* dX, int64_t ldx, void* workspace,
+                                size_t workspace_bytes, void* stream);
+
 /* Bytes of workspace roast_mm_bwd_dM can use for these sizes and mode (0 = none).
  * DETERMINISTIC: required.  ATOMIC: optional -- with it (bf16 path, contraction split over several
  * workgroups) the per-split products are summed in the workspace and scattered with one atomic per

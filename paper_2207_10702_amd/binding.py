@@ -14,10 +14,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libroast_hip.so")
 
 ROAST_F32, ROAST_BF16 = 0, 1
+ROAST_OK, ROAST_ERR_ARG, ROAST_ERR_SHAPE, ROAST_ERR_RANGE, ROAST_ERR_WORKSPACE, ROAST_ERR_HIP, ROAST_ERR_UNSUPPORTED = range(7)
 ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
-           "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
+           "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx",
+           "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
+           "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd", "roast_optim_step"]
 
 
@@ -76,6 +79,11 @@ def load() -> C.CDLL:
     lib.roast_m_shadow_bf16.argtypes = [vp, i64, vp, vp]
     lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
+    for name in ("roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace"):
+        getattr(lib, name).argtypes = [MP, i32, i64]
+        getattr(lib, name).restype = sz
+    lib.roast_mm_fwd_ws.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+    lib.roast_mm_bwd_dx_ws.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
     lib.roast_mm_bwd_dM_workspace.argtypes = [MP, i64, i32]
     lib.roast_mm_bwd_dM_workspace.restype = sz
     lib.roast_mm_bwd_dM.argtypes = [MP, i32, i64, vp, i64, vp, i64, vp, i32, vp, sz, vp]
@@ -87,7 +95,7 @@ def load() -> C.CDLL:
     for name in EXPORTS:
         f = getattr(lib, name)
         if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
-                        "roast_embed_bwd_workspace"):
+                        "roast_embed_bwd_workspace", "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace"):
             f.restype = i32
     _lib = lib
     return lib
@@ -207,7 +215,26 @@ def _shadow_ptr(M, M_bf16) -> int:
     return _vec(M_bf16, torch.bfloat16, "M_bf16")
 
 
-def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None):
+def _ws(ws):
+    return (0, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+def roast_mm_fwd_workspace(desc: RoastMMDesc, dtype, I: int) -> int:
+    """Bytes of workspace that help roast_mm_fwd(..., ws=) at these sizes (0: none)."""
+    torch = _torch()
+    code = {torch.float32: ROAST_F32, torch.bfloat16: ROAST_BF16}[dtype]
+    return int(load().roast_mm_fwd_workspace(C.byref(desc), code, int(I)))
+
+
+def roast_mm_bwd_dx_workspace(desc: RoastMMDesc, dtype, I: int) -> int:
+    torch = _torch()
+    code = {torch.float32: ROAST_F32, torch.bfloat16: ROAST_BF16}[dtype]
+    return int(load().roast_mm_bwd_dx_workspace(C.byref(desc), code, int(I)))
+
+
+def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None, ws=None):
+    """`ws` (optional): uint8 device tensor of at least roast_mm_fwd_workspace(...) bytes; the call then
+    goes through roast_mm_fwd_ws."""
     torch = _torch()
     I = X.shape[0]
     if X.shape[1] != desc.H:
@@ -218,12 +245,16 @@ def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None):
         raise ValueError("Y must be I x O with X's dtype")
     xp, ldx = _mat(X, "X")
     yp, ldy = _mat(Y, "Y")
+    if ws is not None:
+        _check(load().roast_mm_fwd_ws(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"),
+                                      _shadow_ptr(M, M_bf16), yp, ldy, *_ws(ws), _stream(stream)), "roast_mm_fwd_ws")
+        return Y
     _check(load().roast_mm_fwd(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"),
                                _shadow_ptr(M, M_bf16), yp, ldy, _stream(stream)), "roast_mm_fwd")
     return Y
 
 
-def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None):
+def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None, ws=None):
     torch = _torch()
     I = dY.shape[0]
     if dY.shape[1] != desc.O:
@@ -234,6 +265,11 @@ def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None)
         raise ValueError("dX must be I x H with dY's dtype")
     gp, ldy = _mat(dY, "dY")
     xp, ldx = _mat(dX, "dX")
+    if ws is not None:
+        _check(load().roast_mm_bwd_dx_ws(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"),
+                                         _shadow_ptr(M, M_bf16), xp, ldx, *_ws(ws), _stream(stream)),
+               "roast_mm_bwd_dx_ws")
+        return dX
     _check(load().roast_mm_bwd_dx(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"),
                                   _shadow_ptr(M, M_bf16), xp, ldx, _stream(stream)), "roast_mm_bwd_dx")
     return dX

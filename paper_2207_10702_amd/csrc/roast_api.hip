@@ -109,8 +109,23 @@ roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, v
   return shadow_bf16_launch(M, m_size, shadow, (hipStream_t)stream);
 }
 
-roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
-                          const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream) {
+size_t roast_mm_fwd_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I) {
+  MMArgs a;
+  if (make_mm_args(d, I, &a) != ROAST_OK || dt != ROAST_BF16 || I == 0) return 0;
+  const int s = mfma_fwd_splits(a);
+  return s > 1 ? (size_t)s * (size_t)I * (size_t)a.O * sizeof(float) : 0;
+}
+
+size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I) {
+  MMArgs a;
+  if (make_mm_args(d, I, &a) != ROAST_OK || dt != ROAST_BF16 || I == 0) return 0;
+  const int s = mfma_dx_splits(a);
+  return s > 1 ? (size_t)s * (size_t)I * (size_t)a.H * sizeof(float) : 0;
+}
+
+roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                             const float* M, const void* M_bf16, void* Y, int64_t ldy, void* workspace,
+                             size_t workspace_bytes, void* stream) {
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -118,14 +133,22 @@ roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, con
   if (I == 0) return ROAST_OK;
   if (!X || !M || !Y || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
   if (dt == ROAST_BF16) {
-    st = mfma_mm_fwd(a, X, ldx, M, M_bf16, Y, ldy, (hipStream_t)stream);
+    const size_t need = roast_mm_fwd_workspace(d, dt, I);
+    if (workspace && (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0)) return ROAST_ERR_WORKSPACE;
+    st = mfma_mm_fwd(a, X, ldx, M, M_bf16, Y, ldy, need ? (float*)workspace : nullptr, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
   }
   return generic_mm_fwd(a, dt, X, ldx, M, Y, ldy, (hipStream_t)stream);
 }
 
-roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
-                             const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream) {
+roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
+                          const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream) {
+  return roast_mm_fwd_ws(d, dt, I, X, ldx, M, M_bf16, Y, ldy, nullptr, 0, stream);
+}
+
+roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
+                                const float* M, const void* M_bf16, void* dX, int64_t ldx, void* workspace,
+                                size_t workspace_bytes, void* stream) {
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -133,10 +156,17 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
   if (I == 0) return ROAST_OK;
   if (!dY || !M || !dX || ldx < a.H || ldy < a.O) return ROAST_ERR_ARG;
   if (dt == ROAST_BF16) {
-    st = mfma_mm_bwd_dx(a, dY, ldy, M, M_bf16, dX, ldx, (hipStream_t)stream);
+    const size_t need = roast_mm_bwd_dx_workspace(d, dt, I);
+    if (workspace && (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0)) return ROAST_ERR_WORKSPACE;
+    st = mfma_mm_bwd_dx(a, dY, ldy, M, M_bf16, dX, ldx, need ? (float*)workspace : nullptr, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
   }
   return generic_mm_bwd_dx(a, dt, dY, ldy, M, dX, ldx, (hipStream_t)stream);
+}
+
+roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
+                             const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream) {
+  return roast_mm_bwd_dx_ws(d, dt, I, dY, ldy, M, M_bf16, dX, ldx, nullptr, 0, stream);
 }
 
 size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode) {

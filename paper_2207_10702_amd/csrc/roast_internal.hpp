@@ -73,6 +73,18 @@ inline int dm_pick_splits(int64_t tiles, int64_t I) {
   }
   return best;
 }
+// Parts of the contraction axis (length K) for the forward / dX products when a workspace for fp32
+// partial outputs is given: same model, plus about 8 steps for the pass that sums the parts.
+inline int mm_pick_splits(int64_t tiles, int64_t K) {
+  const int64_t steps = (K + 63) / 64;
+  int best = 1;
+  int64_t best_cost = INT64_MAX;
+  for (int s = 1; s <= 16 && (s == 1 || steps / s >= 4); ++s) {
+    const int64_t cost = ((tiles * s + 255) / 256) * ((steps + s - 1) / s + 8) + (s > 1 ? 8 : 0);
+    if (cost < best_cost) { best_cost = cost; best = s; }
+  }
+  return best;
+}
 size_t dm_ws_workspace_bytes(const MMArgs& a);           // 0: not applicable (direct atomics are used)
 roast_status dm_ws_run(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM, void* ws,
                        hipStream_t s);
@@ -89,10 +101,14 @@ roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t 
 // M_bf16 (optional): bf16 copy of M made by shadow_bf16_launch; halves the weight traffic.
 int64_t shadow_stride(int64_t m_size);   // elements between the two copies of the bf16 shadow (a multiple of 64)
 roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s);
+// ws (optional): room for mfma_*_splits() fp32 partial outputs [parts][I][columns]; when given and the
+// shape has too few output tiles to fill the chip, the contraction axis is split over workgroups.
+int mfma_fwd_splits(const MMArgs& a);    // 1: no split (or shape not handled by these kernels)
+int mfma_dx_splits(const MMArgs& a);
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
-                         int64_t ldy, hipStream_t s);
+                         int64_t ldy, float* ws, hipStream_t s);
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
-                            void* dX, int64_t ldx, hipStream_t s);
+                            void* dX, int64_t ldx, float* ws, hipStream_t s);
 // Gws == nullptr: atomically add lambda*sign*G into dM.  Gws != nullptr: store raw per-split G there
 // ([splits][H][O] floats) for the deterministic reduction; `splits` must equal dm_det_splits().
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,

@@ -43,6 +43,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
+typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint32_t uint2v __attribute__((ext_vector_type(2)));
 
 struct __attribute__((packed, aligned(4))) f4u {  // 4 floats, 4-byte aligned (tile bases are arbitrary)
@@ -60,7 +61,8 @@ struct __attribute__((packed, aligned(4))) h8a {
 };
 
 constexpr int BK = 64;
-constexpr int kMaxTable = 512;  // tile-table entries a workgroup may need
+constexpr int kBM = 256, kBN = 128;   // workgroup tile of every kernel here
+constexpr int kMaxTable = 2048; // tile-table entries a workgroup may need
 enum { MODE_FWD = 0, MODE_DX = 1, MODE_DM = 2 };
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
@@ -91,7 +93,8 @@ struct KernArgs {
   int64_t ldc;
   float* dM;           // DM, atomic mode
   float* G;            // DM, deterministic mode: raw products [split][H][O]
-  int rows_per_split;  // DM
+                       // FWD / DX with a split contraction: fp32 partial outputs [split][I][columns]
+  int rows_per_split;  // length of one part of the contraction axis (DM always; FWD / DX when nbz > 1)
   int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
 };
 
@@ -232,9 +235,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   const int Mdim = MODE == MODE_DM ? (int)a.H : I;
   const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
-  if (MODE == MODE_DM) {
+  if (MODE == MODE_DM || p.nbz > 1) {
     k_begin = bz * p.rows_per_split;
-    k_end = min(I, k_begin + p.rows_per_split);
+    k_end = min(k_end, k_begin + p.rows_per_split);
   }
   const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
 
@@ -595,6 +598,33 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
     // Each wave stages one 32-row block at a time in its own LDS buffer and writes it out 16 bytes
     // per lane, row-contiguous.
+    if (p.G != nullptr) {
+      // split contraction: this workgroup's fp32 partial tile goes to its part of the workspace
+      constexpr int ES = WTN * 4 + 16;          // bytes per staged row
+      constexpr int CPR = WTN / 4, RPI = 64 / CPR;
+      static_assert(NC * 32 * ES <= TILES_BYTES, "fp32 epilogue staging must fit in the operand stages");
+      char* ebuf = smem + wave * (32 * ES);
+      float* part = p.G + (int64_t)bz * Mdim * Ndim;
+#pragma unroll
+      for (int i = 0; i < MI; ++i) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            float4v w = {a.lambda * acc[i][j][4 * q], a.lambda * acc[i][j][4 * q + 1],
+                         a.lambda * acc[i][j][4 * q + 2], a.lambda * acc[i][j][4 * q + 3]};
+            *reinterpret_cast<float4v*>(ebuf + (lane & 31) * ES + (j * 32 + 8 * q + 4 * (lane >> 5)) * 4) = w;
+          }
+#pragma unroll
+        for (int it = 0; it < 32 / RPI; ++it) {
+          const int r = it * RPI + lane / CPR, cc = lane % CPR;
+          const float4v v = *reinterpret_cast<const float4v*>(ebuf + r * ES + cc * 16);
+          const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 4;
+          if (row < Mdim && col < Ndim) *reinterpret_cast<float4v*>(part + (int64_t)row * Ndim + col) = v;
+        }
+      }
+      return;
+    }
     char* ebuf = smem + wave * (32 * EPI_STRIDE);
     constexpr int CPR = WTN / 8;              // 16-byte chunks per row of the wave tile
     constexpr int RPI = 64 / CPR;             // rows per store instruction
@@ -681,6 +711,24 @@ __global__ __launch_bounds__(256) void k_shadow_bf16(const float* __restrict__ M
   out[stride + i] = nxt;
 }
 
+// C[r][c] = bf16(sum over the parts, in order, of G[part][r][c]); eight columns per thread
+__global__ __launch_bounds__(256) void k_split_finish(const float* __restrict__ G, int parts, int64_t rows,
+                                                      int64_t cols, uint16_t* __restrict__ C, int64_t ldc) {
+  const int64_t cpr = cols / 8;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= rows * cpr) return;
+  const int64_t r = t / cpr, c = (t % cpr) * 8;
+  float4v s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+  for (int q = 0; q < parts; ++q) {
+    const float4v* g = reinterpret_cast<const float4v*>(G + ((int64_t)q * rows + r) * cols + c);
+    s0 += g[0];
+    s1 += g[1];
+  }
+  const uint4v v = {pack_bf16x2(s0[0], s0[1]), pack_bf16x2(s0[2], s0[3]), pack_bf16x2(s1[0], s1[1]),
+                    pack_bf16x2(s1[2], s1[3])};
+  *reinterpret_cast<uint4v*>(C + r * ldc + c) = v;
+}
+
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -697,35 +745,70 @@ roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hi
   return hip_status(hipGetLastError());
 }
 
+namespace {
+
+// Sets up a split of the contraction axis (length K) into `splits` parts of whole 64-steps.
+void split_setup(KernArgs* p, dim3* grid, int64_t K, int splits, float* ws) {
+  if (splits <= 1 || ws == nullptr) return;
+  p->rows_per_split = (int)(cdiv(cdiv(K, splits), BK) * BK);
+  p->G = ws;
+  grid->z = (unsigned)cdiv(K, p->rows_per_split);
+}
+
+roast_status split_finish(const KernArgs& p, unsigned parts, int64_t rows, int64_t cols, hipStream_t s) {
+  if (p.G == nullptr) return ROAST_OK;
+  const int64_t blocks = cdiv(rows * (cols / 8), 256);
+  if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_split_finish, dim3((unsigned)blocks), dim3(256), 0, s, p.G, (int)parts, rows, cols, p.C, p.ldc);
+  return hip_status(hipGetLastError());
+}
+
+bool mfma_fwd_ok(const MMArgs& a) {
+  return a.Z1 % BK == 0 && a.H % a.Z1 == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
+         a.nTx * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
+}
+bool mfma_dx_ok(const MMArgs& a) {
+  return a.Z2 % BK == 0 && a.O % a.Z2 == 0 && a.H % 8 == 0 && a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
+}
+
+}  // namespace
+
+int mfma_fwd_splits(const MMArgs& a) {
+  return mfma_fwd_ok(a) ? mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), a.H) : 1;
+}
+int mfma_dx_splits(const MMArgs& a) {
+  return mfma_dx_ok(a) ? mm_pick_splits(cdiv(a.H, kBN) * cdiv(a.I, kBM), a.O) : 1;
+}
+
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
-                         int64_t ldy, hipStream_t s) {
-  if (a.Z1 % BK != 0 || a.H % a.Z1 != 0 || a.Z2 % 4 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
-      !aligned16(X) || !aligned16(Y))
+                         int64_t ldy, float* ws, hipStream_t s) {
+  if (!mfma_fwd_ok(a) || ldx % 8 != 0 || ldy % 8 != 0 || !aligned16(X) || !aligned16(Y))
     return ROAST_ERR_UNSUPPORTED;
-  constexpr int BM = 256, BN = 128;
-  if (a.nTx * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  constexpr int BM = kBM, BN = kBN;
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.M = M; p.Mb = (const uint16_t*)M_bf16;
   p.mb_stride = shadow_stride(a.m_size); p.C = (uint16_t*)Y; p.ldc = ldy;
-  const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
+  dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
+  split_setup(&p, &grid, a.H, mfma_fwd_splits(a), ws);
   // the shadow is read in 8-column pieces, which must not straddle tiles
-  if (M_bf16 && a.Z2 % 8 == 0) return launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s);
-  return launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
+  const roast_status st = (M_bf16 && a.Z2 % 8 == 0) ? launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s)
+                                                    : launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
+  return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
-                            void* dX, int64_t ldx, hipStream_t s) {
-  if (a.Z2 % BK != 0 || a.O % a.Z2 != 0 || a.H % 8 != 0 || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) ||
-      !aligned16(dX))
+                            void* dX, int64_t ldx, float* ws, hipStream_t s) {
+  if (!mfma_dx_ok(a) || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) || !aligned16(dX))
     return ROAST_ERR_UNSUPPORTED;
-  constexpr int BM = 256, BN = 128;
-  if (a.nTy * (cdiv(BN, a.Z1) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  constexpr int BM = kBM, BN = kBN;
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)dY; p.lda = ldy; p.M = M; p.Mb = (const uint16_t*)M_bf16;
   p.mb_stride = shadow_stride(a.m_size); p.C = (uint16_t*)dX; p.ldc = ldx;
-  const dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
-  if (M_bf16) return launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s);
-  return launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
+  dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
+  split_setup(&p, &grid, a.O, mfma_dx_splits(a), ws);
+  const roast_status st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s)
+                                 : launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
+  return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,

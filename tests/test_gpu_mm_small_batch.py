@@ -1,0 +1,102 @@
+"""GPU parity of the small-batch variants of the forward and dX products (contraction axis split over
+workgroups, fp32 partial outputs summed in a workspace): same oracle, same bf16 bar as the plain
+calls; bit-reproducible from call to call; the workspace contract is enforced."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2207_10702_amd import workloads as wl
+from tests.util import BF16_TOL, rel_err, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+# (I, H, O, Z1, Z2, |M|, forward splits?, dX splits?)
+SHAPES = [
+    (512, 2048, 512, 64, 64, 50000, True, False),     # long H: forward splits, dX does not
+    (512, 512, 2048, 64, 64, 30000, False, True),     # long O: dX splits
+    (300, 1088, 200, 64, 8, 7001, True, False),       # 17 steps in 4 parts (5, 5, 5, 2); ragged rows and columns
+    (130, 1536, 1536, 128, 128, 100000, True, True),  # both, 128-wide hash tiles
+    (64, 4096, 128, 64, 64, 4096, True, False),       # one output tile, |M| == one hash tile
+]
+
+
+def case(seed, I, H, O, Z1, Z2, m, lam):
+    rng = np.random.default_rng(seed)
+    M = wl.draw_m(rng, m, ("normal", 0.05))
+    X = wl.draw_act(rng, I, H, "bf16")
+    dY = wl.draw_act(rng, I, O, "bf16")
+    h = wl.draw_hash(rng, use_sign=True, align=1)
+    return M, X, dY, h, np.float32(lam)
+
+
+def ws_tensor(nbytes):
+    return torch.empty(max(nbytes, 16), dtype=torch.uint8, device="cuda")
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("pad", [0, 8])
+def test_split_contraction_matches_oracle(roast, shape, pad):
+    I, H, O, Z1, Z2, m, fsplit, xsplit = shape
+    M, X, dY, h, lam = case(900 + I, I, H, O, Z1, Z2, m, 0.41)
+    d = roast.mm_desc(H, O, Z1, Z2, m, 3, lam, h)
+    nf = roast.roast_mm_fwd_workspace(d, torch.bfloat16, I)
+    nx = roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, I)
+    assert (nf > 0) == fsplit and (nx > 0) == xsplit
+    assert nf % (I * O * 4) == 0 and nx % (I * H * 4) == 0          # whole fp32 partial outputs
+    Md = to_dev(M)
+    Mb = roast.roast_m_shadow_bf16(Md)
+    Xd = torch.zeros((I, H + pad), dtype=torch.bfloat16, device="cuda")[:, :H]
+    Xd.copy_(to_dev(X))
+    dYd = torch.zeros((I, O + pad), dtype=torch.bfloat16, device="cuda")[:, :O]
+    dYd.copy_(to_dev(dY))
+    wf, wx = ws_tensor(nf), ws_tensor(nx)
+    outs = []
+    for rep in range(2):
+        Y = torch.full((I, O + pad), 7.0, dtype=torch.bfloat16, device="cuda")[:, :O]
+        dX = torch.full((I, H + pad), 7.0, dtype=torch.bfloat16, device="cuda")[:, :H]
+        wf.fill_(0xFF)                                              # stale workspace contents must not matter
+        wx.fill_(0xFF)
+        roast.roast_mm_fwd(d, Xd, Md, Y, M_bf16=Mb if rep == 0 else None, ws=wf)
+        roast.roast_mm_bwd_dx(d, dYd, Md, dX, M_bf16=Mb if rep == 0 else None, ws=wx)
+        outs.append((Y, dX))
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    if pad:   # nothing is written between the rows
+        assert torch.all(outs[0][0]._base[:, O:] == 7.0) and torch.all(outs[0][1]._base[:, H:] == 7.0)
+
+    Xo, dYo = wl.act_as_f64(X), wl.act_as_f64(dY)
+    W = oracle.materialize_w(h, 3, H, O, Z1, Z2, float(lam), M)
+    assert rel_err(to_host_f64(outs[0][0]), oracle.mm_fwd(Xo, W)) <= BF16_TOL
+    assert rel_err(to_host_f64(outs[0][1]), oracle.mm_bwd_dx(dYo, W)) <= BF16_TOL
+
+    # the plain calls (no split) agree with the split ones to bf16 rounding of the same sums
+    Yp = roast.roast_mm_fwd(d, Xd, Md, M_bf16=Mb)
+    dXp = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=Mb)
+    assert rel_err(to_host_f64(outs[0][0]), to_host_f64(Yp)) <= 2.0 ** -7
+    assert rel_err(to_host_f64(outs[0][1]), to_host_f64(dXp)) <= 2.0 ** -7
+
+
+def test_workspace_contract(roast):
+    I, H, O, Z1, Z2, m = 512, 2048, 512, 64, 64, 50000
+    M, X, dY, h, lam = case(5, I, H, O, Z1, Z2, m, 1.0)
+    d = roast.mm_desc(H, O, Z1, Z2, m, 0, lam, h)
+    need = roast.roast_mm_fwd_workspace(d, torch.bfloat16, I)
+    assert need > 0
+    Md, Xd = to_dev(M), to_dev(X)
+    with pytest.raises(roast.RoastError) as e:
+        roast.roast_mm_fwd(d, Xd, Md, ws=ws_tensor(need - 16))
+    assert e.value.status == roast.ROAST_ERR_WORKSPACE
+    with pytest.raises(roast.RoastError) as e:
+        roast.roast_mm_fwd(d, Xd, Md, ws=ws_tensor(need + 16)[4:])   # misaligned
+    assert e.value.status == roast.ROAST_ERR_WORKSPACE
+    # fp32 and large-batch calls need none and ignore what they are given
+    assert roast.roast_mm_fwd_workspace(d, torch.float32, I) == 0
+    assert roast.roast_mm_fwd_workspace(d, torch.bfloat16, 16384) == 0
+    assert roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, 0) == 0
+    Xf = Xd.to(torch.float32)
+    Y1 = roast.roast_mm_fwd(d, Xf, Md, ws=ws_tensor(16))
+    Y2 = roast.roast_mm_fwd(d, Xf, Md)
+    torch.cuda.synchronize()
+    assert torch.equal(Y1, Y2)
