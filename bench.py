@@ -42,10 +42,12 @@ def parse():
     p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
     p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
     p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
-    p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg3_bert_stack_bf16", "cfg5_large_bf16"],
+    p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg3_bert_stack_bf16", "cfg5_large_bf16",
+                                           "dim_sweep_b512"],
                    default="default",
                    help="default = the headline step (cfg2 ROAST-MM + cfg4 lookup); the others time forward, dX and "
-                        "dM of every layer of another ROAST-MM configuration (a secondary figure, same JSON shape)")
+                        "dM of every layer of another ROAST-MM configuration (a secondary figure, same JSON shape); "
+                        "dim_sweep_b512 = square Dim x Dim layers at batch 512 with a dense bf16 GEMM beside each")
     p.add_argument("--dm-workspace", action="store_true",
                    help="atomic mode only: give roast_mm_bwd_dM its optional scratch (contraction parts x H x O "
                         "floats per call); about 7 %% faster dM, but a buffer of the size of the virtual weights, "
@@ -141,6 +143,76 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
                          "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None}}
 
 
+def bench_dim_sweep(args, roast, wl, torch, np):
+    """Square Dim x Dim ROAST-MM layers at batch 512 (the shape family of the paper's Table 1 and
+    Appendix B), |M| from 4 MB to 512 MB, bf16 with 64x64 tiles: forward, dX, dM and the optimizer
+    step, each timed alone, with the vendor dense bf16 GEMM of the same shape beside them.  The
+    printed Dim 8096 is run as 8192 (a multiple of the tile)."""
+    I, Z = 512, 64
+    dims = [512, 1024, 2048, 4096, 8192, 10240, 20480]
+    m_sizes = [1 << 20, 16 << 20, 128 << 20]
+    g = torch.Generator(device="cuda").manual_seed(2207)
+    hp = wl.draw_hash(np.random.default_rng(10702), use_sign=True, align=1)
+
+    def timed(fn, reps):
+        for _ in range(max(2, args.warmup // 3)):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    Ms = {m: torch.randn(m, dtype=torch.float32, device="cuda", generator=g) * 0.02 for m in m_sizes}
+    shadows = {m: roast.roast_m_shadow_bf16(Ms[m]) for m in m_sizes}
+    dM = torch.zeros(max(m_sizes), dtype=torch.float32, device="cuda")
+    for dim in dims:
+        reps = max(5, min(args.steps, int(4e6 / dim)))
+        X = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
+        dY = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
+        Y, dX = torch.empty_like(X), torch.empty_like(X)
+        W = (torch.randn((dim, dim), dtype=torch.float32, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        dW = torch.empty_like(W)
+        row = {"Dim": dim, "GFLOP_per_product": 2.0 * I * dim * dim / 1e9,
+               "dense_fwd_ms": timed(lambda: torch.matmul(X, W, out=Y), reps),
+               "dense_dx_ms": timed(lambda: torch.matmul(dY, W.t(), out=dX), reps),
+               "dense_dw_ms": timed(lambda: torch.matmul(X.t(), dY, out=dW), reps), "roast": {}}
+        del W, dW
+        for m in m_sizes:
+            d = roast.mm_desc(dim, dim, Z, Z, m, 0, 1.0, hp)
+            nbytes = max(roast.roast_mm_fwd_workspace(d, torch.bfloat16, I),
+                         roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, I), 16)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+            M, Mb, dMv = Ms[m], shadows[m], dM[:m]
+            r = {"fwd_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb, ws=ws), reps),
+                 "fwd_no_ws_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb), reps),
+                 "dx_ms": timed(lambda: roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb, ws=ws), reps),
+                 "dM_ms": timed(lambda: roast.roast_mm_bwd_dM(d, X, dY, dMv, roast.ROAST_REDUCE_ATOMIC), reps),
+                 "workspace_MB": nbytes / 1e6}
+            row["roast"][f"{m * 4 >> 20}MB"] = r
+            del ws
+        rows.append(row)
+        print(f"# Dim {dim}: dense fwd {row['dense_fwd_ms']:.3f} ms; ROAST fwd "
+              + " / ".join(f"{v['fwd_ms']:.3f}" for v in row["roast"].values()) + " ms", file=sys.stderr, flush=True)
+    last = rows[-1]
+    best = last["roast"]["4MB"]["fwd_ms"]
+    tflops = last["GFLOP_per_product"] / best
+    avg = lambda key, m: sum(r["roast"][m][key] for r in rows) / len(rows)
+    return {"metric": "ROAST-MM forward TFLOP/s at Dim 20480, batch 512, |M| 4 MB", "unit": "TFLOP/s", "value": tflops,
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "dim_sweep_b512: square Dim x Dim, batch 512, 64x64 tiles, |M| 4 / 64 / 512 MB"},
+            "averages_ms": {m: {k: avg(k, m) for k in ("fwd_ms", "dx_ms", "dM_ms")} for m in last["roast"]},
+            "dense_averages_ms": {k: sum(r[k] for r in rows) / len(rows)
+                                  for k in ("dense_fwd_ms", "dense_dx_ms", "dense_dw_ms")},
+            "table": rows,
+            "roofline": {"kernel": "roast_mm_fwd at Dim 20480", "bound": "mfma", "achieved": tflops,
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None}}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -156,6 +228,9 @@ def main():
     roast.load()
     torch.cuda.set_device(0)
     mode = roast.ROAST_REDUCE_ATOMIC if args.reduce == "atomic" else roast.ROAST_REDUCE_DETERMINISTIC
+    if args.workload == "dim_sweep_b512":
+        print(json.dumps(bench_dim_sweep(args, roast, wl, torch, np)))
+        return
     if args.workload != "default":
         print(json.dumps(bench_mm_config(args, roast, wl, torch, np, to_dev, mode)))
         return
