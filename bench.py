@@ -154,8 +154,8 @@ def bench_dim_sweep(args, roast, wl, torch, np):
     g = torch.Generator(device="cuda").manual_seed(2207)
     hp = wl.draw_hash(np.random.default_rng(10702), use_sign=True, align=1)
 
-    def timed(fn, reps):
-        for _ in range(max(2, args.warmup // 3)):
+    def timed(fn, reps, warm=None):
+        for _ in range(max(2, args.warmup // 3) if warm is None else warm):
             fn()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
@@ -194,9 +194,21 @@ def bench_dim_sweep(args, roast, wl, torch, np):
                  "workspace_MB": nbytes / 1e6}
             row["roast"][f"{m * 4 >> 20}MB"] = r
             del ws
+        # element-wise hashing (1x1 tiles, one hash per virtual weight): the HashedNet-style map the
+        # paper compares against, run through the same entry points (generic kernels)
+        row["elementwise_1x1"] = {}
+        for m in (m_sizes[0], m_sizes[-1]):
+            d = roast.mm_desc(dim, dim, 1, 1, m, 0, 1.0, hp)
+            M, dMv = Ms[m], dM[:m]
+            row["elementwise_1x1"][f"{m * 4 >> 20}MB"] = {
+                "fwd_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y), 3, 1),
+                "dx_ms": timed(lambda: roast.roast_mm_bwd_dx(d, dY, M, dX), 3, 1),
+                "dM_ms": timed(lambda: roast.roast_mm_bwd_dM(d, X, dY, dMv, roast.ROAST_REDUCE_ATOMIC), 3, 1)}
         rows.append(row)
         print(f"# Dim {dim}: dense fwd {row['dense_fwd_ms']:.3f} ms; ROAST fwd "
-              + " / ".join(f"{v['fwd_ms']:.3f}" for v in row["roast"].values()) + " ms", file=sys.stderr, flush=True)
+              + " / ".join(f"{v['fwd_ms']:.3f}" for v in row["roast"].values()) + " ms; 1x1 tiles fwd "
+              + " / ".join(f"{v['fwd_ms']:.3f}" for v in row["elementwise_1x1"].values()) + " ms",
+              file=sys.stderr, flush=True)
     last = rows[-1]
     best = last["roast"]["4MB"]["fwd_ms"]
     tflops = last["GFLOP_per_product"] / best
@@ -208,6 +220,8 @@ def bench_dim_sweep(args, roast, wl, torch, np):
             "averages_ms": {m: {k: avg(k, m) for k in ("fwd_ms", "dx_ms", "dM_ms")} for m in last["roast"]},
             "dense_averages_ms": {k: sum(r[k] for r in rows) / len(rows)
                                   for k in ("dense_fwd_ms", "dense_dx_ms", "dense_dw_ms")},
+            "elementwise_over_tiled_fwd": {m: sum(r["elementwise_1x1"][m]["fwd_ms"] for r in rows)
+                                           / sum(r["roast"][m]["fwd_ms"] for r in rows) for m in ("4MB", "512MB")},
             "table": rows,
             "roofline": {"kernel": "roast_mm_fwd at Dim 20480", "bound": "mfma", "achieved": tflops,
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None}}
