@@ -23,3 +23,4 @@ from .roast_oracle import (  # noqa: F401
     num_threads,
 )
 from . import optim_oracle as optim  # noqa: F401,E402
+from .bag_oracle import embed_bag_fwd, embed_bag_bwd  # noqa: F401,E402
