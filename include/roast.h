@@ -213,6 +213,32 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
                              roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Pooled (bag-sum) lookup: the lookup L of Section 3.1 applied to every id of a bag, summed per bag
+ * (the multi-hot use of an embedding table):
+ *   out[b, :] = sum over n in [bag_offsets[b], bag_offsets[b+1]) of the row roast_embed_fwd returns
+ *               for (rows[n], table_ids[n]);   out: B x D fp32 (row stride D), overwritten.
+ * bag_offsets: DEVICE array of B + 1 int64: bag_offsets[0] = 0, non-decreasing, bag_offsets[B] = N;
+ * an empty bag gives a zero row.  The library cannot check device data: offsets that break the
+ * contract give unspecified values in `out` / `dM`, but every access stays inside the arrays.
+ * Sums run in lookup order: results are bit-reproducible.
+ */
+roast_status roast_embed_bag_fwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
+                                 const uint32_t* table_ids, const int64_t* bag_offsets, const float* M,
+                                 float* out, void* stream);
+
+/* Workspace of roast_embed_bag_bwd; same meaning as roast_embed_bwd_workspace. */
+size_t roast_embed_bag_bwd_workspace(const roast_embed_desc* d, int64_t N, int64_t B, roast_reduce_mode mode);
+
+/*
+ * Gradient of the pooled lookup (Section 3.3 applied to a sum: every lookup of bag b receives
+ * dOut[b, :]):  dM[offset(t,r,c) + o] += lambda * sign * dOut[bag(n), c*Z + o]  for all n.
+ * dOut: B x D fp32 (row stride D); dM, mode, ws / ws_bytes as for roast_embed_bwd.
+ */
+roast_status roast_embed_bag_bwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
+                                 const uint32_t* table_ids, const int64_t* bag_offsets, const float* dOut,
+                                 float* dM, roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Optimizer step on the shared array: the "update weights" leg of the paper's training workload
  * (training-time tables of the appendix: SGD, Adagrad, Adam on the |M|-sized parameter).  The paper
  * defines no update rule of its own; these are the textbook rules in the form of the stock optimizers:

@@ -21,7 +21,8 @@ EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device",
            "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx",
            "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
            "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
-           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd", "roast_optim_step"]
+           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd",
+           "roast_embed_bag_fwd", "roast_embed_bag_bwd_workspace", "roast_embed_bag_bwd", "roast_optim_step"]
 
 
 class RoastError(RuntimeError):
@@ -91,11 +92,16 @@ def load() -> C.CDLL:
     lib.roast_embed_bwd_workspace.argtypes = [EP, i64, i32]
     lib.roast_embed_bwd_workspace.restype = sz
     lib.roast_embed_bwd.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.roast_embed_bag_fwd.argtypes = [EP, i64, i64, vp, vp, vp, vp, vp, vp]
+    lib.roast_embed_bag_bwd_workspace.argtypes = [EP, i64, i64, i32]
+    lib.roast_embed_bag_bwd_workspace.restype = sz
+    lib.roast_embed_bag_bwd.argtypes = [EP, i64, i64, vp, vp, vp, vp, vp, i32, vp, sz, vp]
     lib.roast_optim_step.argtypes = [C.POINTER(RoastOptimDesc), i64, vp, vp, vp, vp, vp, vp]
     for name in EXPORTS:
         f = getattr(lib, name)
         if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
-                        "roast_embed_bwd_workspace", "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace"):
+                        "roast_embed_bwd_workspace", "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace",
+                        "roast_embed_bag_bwd_workspace"):
             f.restype = i32
     _lib = lib
     return lib
@@ -325,6 +331,41 @@ def roast_embed_bwd(desc: RoastEmbedDesc, rows, table_ids, dOut, dM, mode: int =
                                   _vec(table_ids, torch.int32, "table_ids"), _vec(dOut, torch.float32, "dOut"),
                                   _vec(dM, torch.float32, "dM"), int(mode), wp, wb, _stream(stream)),
            "roast_embed_bwd")
+    return dM
+
+
+def roast_embed_bag_fwd(desc: RoastEmbedDesc, rows, table_ids, bag_offsets, M, out=None, stream=None):
+    """Pooled lookup: out[b] = sum of the rows of the lookups [bag_offsets[b], bag_offsets[b+1])."""
+    torch = _torch()
+    N, B = rows.numel(), bag_offsets.numel() - 1
+    if B < 0:
+        raise ValueError("bag_offsets must have B + 1 entries")
+    if out is None:
+        out = torch.empty((B, desc.D), dtype=torch.float32, device=M.device)
+    if tuple(out.shape) != (B, desc.D):
+        raise ValueError("out must be B x D")
+    _check(load().roast_embed_bag_fwd(C.byref(desc), N, B, _vec(rows, torch.int64, "rows"),
+                                      _vec(table_ids, torch.int32, "table_ids"),
+                                      _vec(bag_offsets, torch.int64, "bag_offsets"), _vec(M, torch.float32, "M"),
+                                      _vec(out, torch.float32, "out"), _stream(stream)), "roast_embed_bag_fwd")
+    return out
+
+
+def roast_embed_bag_bwd_workspace(desc: RoastEmbedDesc, N: int, B: int, mode: int = ROAST_REDUCE_ATOMIC) -> int:
+    return int(load().roast_embed_bag_bwd_workspace(C.byref(desc), int(N), int(B), int(mode)))
+
+
+def roast_embed_bag_bwd(desc: RoastEmbedDesc, rows, table_ids, bag_offsets, dOut, dM, mode: int = ROAST_REDUCE_ATOMIC,
+                        ws=None, stream=None):
+    torch = _torch()
+    N, B = rows.numel(), bag_offsets.numel() - 1
+    if B < 0 or tuple(dOut.shape) != (B, desc.D) or dM.numel() != desc.m_size:
+        raise ValueError("dOut must be B x D and dM must have m_size entries")
+    _check(load().roast_embed_bag_bwd(C.byref(desc), N, B, _vec(rows, torch.int64, "rows"),
+                                      _vec(table_ids, torch.int32, "table_ids"),
+                                      _vec(bag_offsets, torch.int64, "bag_offsets"), _vec(dOut, torch.float32, "dOut"),
+                                      _vec(dM, torch.float32, "dM"), int(mode), *_ws(ws), _stream(stream)),
+           "roast_embed_bag_bwd")
     return dM
 
 

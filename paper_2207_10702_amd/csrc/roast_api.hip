@@ -45,6 +45,8 @@ roast_status make_embed_args(const roast_embed_desc* d, int64_t N, EmbedArgs* a)
   a->m_size = d->m_size;
   a->lambda = d->lambda;
   a->hash = make_hash_dev(d->hash, d->m_size, d->Z);
+  a->bag_off = nullptr;
+  a->B = 0;
   return ROAST_OK;
 }
 
@@ -230,6 +232,47 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
   if (!mode_ok(mode)) return ROAST_ERR_ARG;
   if (N == 0) return ROAST_OK;
   if (!rows || !table_ids || !dOut || !dM) return ROAST_ERR_ARG;
+  if (mode == ROAST_REDUCE_DETERMINISTIC) {
+    const size_t need = embed_det_workspace_bytes(a);
+    if (need == 0) return ROAST_ERR_UNSUPPORTED;
+    if (!ws || ws_bytes < need) return ROAST_ERR_WORKSPACE;
+    return embed_bwd_det_run(a, rows, table_ids, dOut, dM, ws, (hipStream_t)stream);
+  }
+  return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, ws, ws_bytes, (hipStream_t)stream);
+}
+
+roast_status roast_embed_bag_fwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
+                                 const uint32_t* table_ids, const int64_t* bag_offsets, const float* M, float* out,
+                                 void* stream) {
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (B < 0) return ROAST_ERR_ARG;
+  if (B == 0) return ROAST_OK;
+  if (!bag_offsets || !M || !out || (N > 0 && (!rows || !table_ids))) return ROAST_ERR_ARG;
+  a.bag_off = bag_offsets;
+  a.B = B;
+  return embed_bag_fwd_launch(a, rows, table_ids, M, out, (hipStream_t)stream);
+}
+
+size_t roast_embed_bag_bwd_workspace(const roast_embed_desc* d, int64_t N, int64_t B, roast_reduce_mode mode) {
+  EmbedArgs a;
+  if (make_embed_args(d, N, &a) != ROAST_OK || B <= 0 || N == 0) return 0;
+  a.B = B;
+  return mode == ROAST_REDUCE_DETERMINISTIC ? embed_det_workspace_bytes(a) : embed_bucket_workspace_bytes(a);
+}
+
+roast_status roast_embed_bag_bwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
+                                 const uint32_t* table_ids, const int64_t* bag_offsets, const float* dOut, float* dM,
+                                 roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream) {
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (!mode_ok(mode) || B < 0) return ROAST_ERR_ARG;
+  if (N == 0 || B == 0) return ROAST_OK;
+  if (!rows || !table_ids || !bag_offsets || !dOut || !dM) return ROAST_ERR_ARG;
+  a.bag_off = bag_offsets;
+  a.B = B;
   if (mode == ROAST_REDUCE_DETERMINISTIC) {
     const size_t need = embed_det_workspace_bytes(a);
     if (need == 0) return ROAST_ERR_UNSUPPORTED;

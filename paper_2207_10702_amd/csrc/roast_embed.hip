@@ -42,6 +42,21 @@ __device__ inline void for_each_chunk(const EmbedArgs& a, bool walk, uint64_t ta
   }
 }
 
+// Pooled gradient: the bag of lookup n = the last b with bag_off[b] <= n (bag_off[0] == 0, so one
+// exists; empty bags share their offset with the next one and are skipped by "last").  The result is
+// clamped to [0, B-1] whatever the offsets hold, so a malformed offsets array cannot push a read out
+// of dOut.
+__device__ inline int64_t bag_of(const int64_t* __restrict__ bag_off, int64_t B, int64_t n) {
+  int64_t lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int64_t mid = (lo + hi) >> 1;
+    if (bag_off[mid] <= n) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+// row of dOut that lookup n takes its gradient from
+__device__ inline int64_t grad_row(const EmbedArgs& a, int64_t n) { return a.bag_off ? bag_of(a.bag_off, a.B, n) : n; }
+
 // Streaming lookup / direct-atomic gradient.  A wave takes 64 lookups: each lane hashes the chunks
 // of one lookup into the wave's LDS key list (offset | sign bit, 32-bit), then the wave walks the
 // 64*C chunks in order, LPI lanes per chunk, VEC floats per lane.
@@ -108,7 +123,7 @@ __global__ __launch_bounds__(256) void k_embed(EmbedArgs a, int lpi_log2, int wa
     const int64_t g = g0 + j;
     const int64_t n = g / C, c = g - n * C;
     const int len = (int)min((int64_t)a.Z, a.D - c * a.Z);   // last chunk of a row may be short
-    const int64_t obase = n * a.D + c * a.Z;
+    const int64_t obase = (BWD ? grad_row(a, n) : n) * a.D + c * a.Z;
     for (int o = sub * VEC; o < len; o += lpi * VEC) {
       if (VEC == 4) {
         if (!BWD) {
@@ -146,7 +161,7 @@ __global__ __launch_bounds__(256) void k_embed_elem(EmbedArgs a, const int64_t* 
   const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
   const float scale = a.lambda * (float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
   if (!BWD) out[e] = scale * M[off + o];
-  else unsafeAtomicAdd(dM + off + o, scale * dOut[e]);
+  else unsafeAtomicAdd(dM + off + o, scale * dOut[grad_row(a, n) * a.D + i]);
 }
 
 __global__ __launch_bounds__(256) void k_chunk_index(EmbedArgs a, int walk, const int64_t* __restrict__ rows,
@@ -158,6 +173,104 @@ __global__ __launch_bounds__(256) void k_chunk_index(EmbedArgs a, int walk, cons
     off[n * a.C + c] = o;
     sgn[n * a.C + c] = (int8_t)s;
   });
+}
+
+// Pooled forward: out[b, :] = lambda * sum over the lookups n of bag b of sign_n * M[offset_n(c) + o].
+// A workgroup owns `bags_wg` consecutive bags, i.e. one contiguous range of lookups.  It works in
+// windows of at most `win` lookups: every lookup of the window is hashed once (one thread per
+// lookup, all its chunks, keys to LDS), then each thread walks the part of its bag that lies in the
+// window and adds its piece (VEC floats of one chunk) of every row -- gathered reads of M, served by
+// L2.  Sums run in lookup order, in fp64, so the result does not depend on the launch shape.
+// VEC = 4 requires Z % 4 == 0 and D % 4 == 0 (a piece never straddles a chunk or the row end).
+template <int VEC>
+__global__ __launch_bounds__(256) void k_embed_bag_fwd(EmbedArgs a, int walk, int tpb, int bags_wg, int win,
+                                                       const int64_t* __restrict__ rows,
+                                                       const uint32_t* __restrict__ tables,
+                                                       const float* __restrict__ M, float* __restrict__ out) {
+  extern __shared__ uint32_t s_bag_keys[];       // [win * C]
+  const int C = (int)a.C;
+  const int64_t b0 = (int64_t)blockIdx.x * bags_wg;
+  const int64_t b1 = min(a.B, b0 + bags_wg);
+  auto clampN = [&](int64_t v) { return min(max(v, (int64_t)0), a.N); };
+  const int64_t n_begin = clampN(a.bag_off[b0]);
+  const int64_t n_end = max(n_begin, clampN(a.bag_off[b1]));
+  const int bl = threadIdx.x / tpb, tl = threadIdx.x % tpb;
+  const int64_t b = b0 + bl;
+  const bool active = bl < bags_wg && b < b1;
+  int64_t my_begin = 0, my_end = 0;
+  if (active) {
+    my_begin = min(max(clampN(a.bag_off[b]), n_begin), n_end);
+    my_end = min(max(clampN(a.bag_off[b + 1]), my_begin), n_end);
+  }
+  const int pieces = (int)((a.D + VEC - 1) / VEC);
+  for (int p0 = 0; p0 < pieces; p0 += tpb) {           // one pass unless a row has more pieces than tpb
+    const int piece = p0 + tl;
+    const bool live = active && piece < pieces;
+    const int c = live ? (piece * VEC) / a.Z : 0, o = live ? (piece * VEC) % a.Z : 0;
+    double acc[VEC];   // a bag may hold thousands of rows: fp64 sums keep the result within one fp32 rounding
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.0;
+    for (int64_t w0 = n_begin; w0 < n_end; w0 += win) {   // uniform trip count for the workgroup
+      const int64_t w1 = min(n_end, w0 + win);
+      __syncthreads();                                    // the previous window's keys are no longer needed
+      for (int64_t n = w0 + threadIdx.x; n < w1; n += 256)
+        for_each_chunk(a, walk != 0, tables[n], (uint64_t)rows[n], [&](int64_t cc, int64_t off, int sgn) {
+          s_bag_keys[(n - w0) * C + cc] = (uint32_t)off | (sgn < 0 ? 0x80000000u : 0u);
+        });
+      __syncthreads();
+      if (!live) continue;
+      const int64_t lo = max(my_begin, w0), hi = min(my_end, w1);
+      constexpr int U = 4;
+      for (int64_t n = lo; n < hi; n += U) {
+        float m[U][VEC];
+        float sg[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int64_t nn = min(n + u, hi - 1);
+          const uint32_t key = s_bag_keys[(nn - w0) * C + c];
+          sg[u] = (n + u < hi) ? ((key & 0x80000000u) ? -1.f : 1.f) : 0.f;
+          const float* src = M + (key & 0x7fffffffu) + o;
+          if constexpr (VEC == 4) {
+            const f4u t = *reinterpret_cast<const f4u*>(src);   // 4-byte aligned: chunk bases are arbitrary
+#pragma unroll
+            for (int v = 0; v < 4; ++v) m[u][v] = t.v[v];
+          } else {
+            m[u][0] = src[0];
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int v = 0; v < VEC; ++v) acc[v] += (double)(sg[u] * m[u][v]);
+      }
+    }
+    if (live) {
+      float* dst = out + b * a.D + (int64_t)piece * VEC;
+      if constexpr (VEC == 4) {
+        const double l = (double)a.lambda;
+        const vfloat4 r = {(float)(l * acc[0]), (float)(l * acc[1]), (float)(l * acc[2]), (float)(l * acc[3])};
+        *reinterpret_cast<vfloat4*>(dst) = r;
+      } else {
+        dst[0] = (float)((double)a.lambda * acc[0]);
+      }
+    }
+  }
+}
+
+// Fallback for huge M or very many chunks per row: one thread per output element.
+__global__ __launch_bounds__(256) void k_embed_bag_fwd_elem(EmbedArgs a, const int64_t* __restrict__ rows,
+                                                            const uint32_t* __restrict__ tables,
+                                                            const float* __restrict__ M, float* __restrict__ out) {
+  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= a.B * a.D) return;
+  const int64_t b = e / a.D, i = e - b * a.D, c = i / a.Z, o = i - c * a.Z;
+  const int64_t n0 = min(max(a.bag_off[b], (int64_t)0), a.N), n1 = min(max(a.bag_off[b + 1], n0), a.N);
+  double acc = 0.0;
+  for (int64_t n = n0; n < n1; ++n) {
+    const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
+    acc += (double)((float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c) * M[off + o]);
+  }
+  out[e] = (float)((double)a.lambda * acc);
 }
 
 inline int walk_ok(const EmbedArgs& a) { return (uint64_t)a.C <= a.hash.P.d ? 1 : 0; }
@@ -219,7 +332,7 @@ inline BucketPlan bucket_plan(const EmbedArgs& a) {
   BucketPlan p{};
   p.n_items = a.N * a.C;
   p.ok = (a.Z % 4 == 0) && (a.D % a.Z == 0) && a.m_size < (1ll << 31) && p.n_items < (1ll << 31) && a.Z <= 1024 &&
-         a.C <= kMaxC;
+         a.C <= kMaxC && a.B * a.C < (1ll << 31);   // (B = 0 unless pooled)
   if (!p.ok) return p;
   int r = 12;
   while ((1 << r) < kMaxR && ((a.m_size + (1ll << r) - 1) >> r) > kMaxBuckets) ++r;
@@ -295,7 +408,7 @@ __global__ __launch_bounds__(256) void k_embed_fixed_elem(EmbedArgs a, int pbits
   const int64_t n = e / a.D, i = e - n * a.D, c = i / a.Z, o = i - c * a.Z;
   const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
   const float sc = a.lambda * (float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
-  atomicAdd(acc + off + o, to_fixed(sc * dOut[e], scale));
+  atomicAdd(acc + off + o, to_fixed(sc * dOut[grad_row(a, n) * a.D + i], scale));
 }
 
 __global__ __launch_bounds__(256) void k_embed_fixed_finish(int64_t m_size, float lambda, int pbits, const FixedScale* fs,
@@ -325,12 +438,14 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
   uint16_t* s_pos = reinterpret_cast<uint16_t*>(s_key + items);   // [items] rank inside (workgroup, bucket)
   uint32_t* hist = s_key + items + items / 2;                      // [nb]  chunks of this workgroup per bucket
   uint32_t* gbase = hist + nb;                                     // [nb]  reserved position in the bucket's global list
+  uint32_t* s_src = gbase + nb;                                    // [rows_wg] gradient row of each lookup (pooled calls only)
   for (int i = threadIdx.x; i < nb; i += 256) hist[i] = 0u;
   __syncthreads();
   const int64_t n0 = (int64_t)blockIdx.x * rows_wg;
   const int rows_here = (int)min((int64_t)rows_wg, a.N - n0);
   for (int q = threadIdx.x; q < rows_here; q += 256) {
     const int64_t n = n0 + q;
+    if (a.bag_off) s_src[q] = (uint32_t)bag_of(a.bag_off, a.B, n);
     for_each_chunk(a, walk != 0, tables[n], (uint64_t)rows[n], [&](int64_t c, int64_t off, int sgn) {
       s_key[q * C + c] = (uint32_t)off | (sgn < 0 ? 0x80000000u : 0u);
       s_pos[q * C + c] = (uint16_t)atomicAdd(&hist[(uint32_t)off >> r_log2], 1u);
@@ -347,7 +462,8 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
     const uint32_t key = s_key[i];
     const uint32_t b = (key & 0x7fffffffu) >> r_log2;
     const uint32_t pos = gbase[b] + s_pos[i];
-    const uint2 e = make_uint2((uint32_t)(n0 * C + i), key);
+    // entry.x = number of the dOut chunk to add: chunk c of lookup n, or of n's bag in a pooled call
+    const uint2 e = make_uint2(a.bag_off ? s_src[i / C] * (uint32_t)C + (uint32_t)(i % C) : (uint32_t)(n0 * C + i), key);
     if (pos < cap) {
       list[(size_t)b * cap + pos] = e;
     } else {
@@ -467,7 +583,7 @@ roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* 
   uint2* list = (uint2*)(base + p.list_off);
   hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, (int64_t)p.nb);
   const int rows_wg = kRouteItems / (int)a.C;
-  const size_t lds_route = (size_t)kRouteItems * (4 + 2) + (size_t)2 * p.nb * 4;
+  const size_t lds_route = (size_t)kRouteItems * (4 + 2) + (size_t)2 * p.nb * 4 + (a.bag_off ? (size_t)rows_wg * 4 : 0);
   static bool configured = false;   // per instantiation
   if (!configured) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
@@ -535,9 +651,10 @@ roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const ui
   const int64_t zb = (zero_words + 255) / 256;
   if (zb > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
   hipLaunchKernelGGL(k_embed_zero, dim3((unsigned)zb), dim3(256), 0, s, (uint32_t*)base, zero_words);
-  const int64_t n_el = a.N * a.D;
-  const int64_t ab = std::min<int64_t>((n_el + 255) / 256, 256 * 32);
-  hipLaunchKernelGGL(k_embed_absmax, dim3((unsigned)ab), dim3(256), 0, s, dOut, n_el, fs);
+  const int64_t n_el = a.N * a.D;                               // contributions
+  const int64_t n_grad = (a.bag_off ? a.B : a.N) * a.D;          // elements of dOut
+  const int64_t ab = std::min<int64_t>((n_grad + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(k_embed_absmax, dim3((unsigned)ab), dim3(256), 0, s, dOut, n_grad, fs);
   const BucketPlan p = bucket_plan(a);
   roast_status st;
   if (bucket_worthwhile(p, dOut)) {
@@ -551,6 +668,31 @@ roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const ui
   if (st != ROAST_OK) return st;
   hipLaunchKernelGGL(k_embed_fixed_finish, dim3((unsigned)((a.m_size + 255) / 256)), dim3(256), 0, s, a.m_size, a.lambda,
                      pbits, fs, acc, dM);
+  return hip_status(hipGetLastError());
+}
+
+roast_status embed_bag_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
+                                  float* out, hipStream_t s) {
+  if (a.m_size >= (1ll << 31) || a.C > kMaxC) {
+    const int64_t blocks = (a.B * a.D + 255) / 256;
+    if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(k_embed_bag_fwd_elem, dim3((unsigned)blocks), dim3(256), 0, s, a, rows, tables, M, out);
+    return hip_status(hipGetLastError());
+  }
+  const bool vec4 = (a.Z % 4 == 0) && (a.D % 4 == 0) && (((uintptr_t)out & 15) == 0);
+  const int64_t pieces = vec4 ? a.D / 4 : a.D;
+  const int tpb = (int)std::min<int64_t>(256, pieces);      // threads per bag
+  const int bags_wg = 256 / tpb;
+  const int win = (int)(8192 / a.C);                        // 32 KiB of keys per window
+  const int64_t blocks = (a.B + bags_wg - 1) / bags_wg;
+  if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  const size_t lds = (size_t)win * a.C * sizeof(uint32_t);
+  if (vec4)
+    hipLaunchKernelGGL(k_embed_bag_fwd<4>, dim3((unsigned)blocks), dim3(256), lds, s, a, walk_ok(a), tpb, bags_wg, win,
+                       rows, tables, M, out);
+  else
+    hipLaunchKernelGGL(k_embed_bag_fwd<1>, dim3((unsigned)blocks), dim3(256), lds, s, a, walk_ok(a), tpb, bags_wg, win,
+                       rows, tables, M, out);
   return hip_status(hipGetLastError());
 }
 

@@ -27,6 +27,10 @@ struct EmbedArgs {
   int64_t m_size;
   float lambda;
   HashDev hash;
+  // pooled (bag-sum) gradient only: lookup n takes its gradient row from dOut[bag of n] instead of
+  // dOut[n]; bag b covers lookups [bag_off[b], bag_off[b+1]).  nullptr / 0 for per-lookup calls.
+  const int64_t* bag_off;
+  int64_t B;
 };
 
 inline roast_status hip_status(hipError_t e) { return e == hipSuccess ? ROAST_OK : ROAST_ERR_HIP; }
@@ -118,6 +122,9 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
 roast_status embed_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
                               float* out, hipStream_t s);
 // ws may be null (or too small): the gradient then goes straight to dM with global atomics.
+// out[b, :] = sum of the rows of the lookups of bag b (a.bag_off, a.B set)
+roast_status embed_bag_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
+                                  float* out, hipStream_t s);
 size_t embed_bucket_workspace_bytes(const EmbedArgs& a);
 roast_status embed_bwd_atomic_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables,
                                      const float* dOut, float* dM, void* ws, size_t ws_bytes, hipStream_t s);
