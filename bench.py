@@ -385,6 +385,32 @@ def main():
                                "roofline": {"kernel": "k_embed (embed_fwd)", "bound": "hbm", "achieved": gbs_f,
                                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
                                             "traffic": MEASURED_TRAFFIC_BYTES.get("embed_fwd")}}
+        # the pooled reading of "gather-sum": one output row per sample = the sum of its 26 lookups
+        nb = N // ecfg.n_tables
+        bag_off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * ecfg.n_tables
+        pout = torch.empty((nb, ecfg.D), dtype=torch.float32, device="cuda")
+        pdOut = dOut[:nb]
+        pws = torch.empty(max(roast.roast_embed_bag_bwd_workspace(ed, N, nb, mode), 1), dtype=torch.uint8, device="cuda")
+
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        pf = timed(lambda: roast.roast_embed_bag_fwd(ed, rows, tables, bag_off, eM, pout))
+        pb = timed(lambda: roast.roast_embed_bag_bwd(ed, rows, tables, bag_off, pdOut, edM, mode, pws))
+        edM.zero_()
+        result["embedding"]["pooled_sum_of_26"] = {
+            "bags": nb, "fwd_ms": pf, "bwd_ms": pb, "lookups_per_s_fwd": N / (pf * 1e-3),
+            "lookups_per_s_bwd": N / (pb * 1e-3),
+            # what the gathers deliver: every lookup reads D floats of M (cache-resident) / of dOut
+            "gathered_GBs_fwd": N * ecfg.D * 4 / (pf * 1e-3) / 1e9, "gathered_GBs_bwd": N * ecfg.D * 4 / (pb * 1e-3) / 1e9}
         if args.embed_only:
             result["value"] = tot
             result["unit"] = "GB/s"

@@ -510,6 +510,46 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
   // dependent loads, so the entries of the next batch are fetched while this batch's chunks load.
   // The body is branch-free: a slot past the end of the list becomes chunk 0 with weight 0.
   constexpr int U = 8;
+  auto add_chunk = [&](uint2 ent, vfloat4 dv) {
+    const bool ok = ent.y != 0xffffffffu;
+    const float sc = !ok ? 0.f : ((ent.y & 0x80000000u) ? -a.lambda : a.lambda);
+    const int rel = (ok ? (int)((int64_t)(ent.y & 0x7fffffffu) - slot0) : 0) + 4 * sub;
+    if constexpr (FIXED) {
+      atomicAdd(&img[rel + 0], to_fixed(sc * dv.x, scale));
+      atomicAdd(&img[rel + 1], to_fixed(sc * dv.y, scale));
+      atomicAdd(&img[rel + 2], to_fixed(sc * dv.z, scale));
+      atomicAdd(&img[rel + 3], to_fixed(sc * dv.w, scale));
+    } else {
+      atomicAdd(&img[rel + 0], (double)(sc * dv.x));
+      atomicAdd(&img[rel + 1], (double)(sc * dv.y));
+      atomicAdd(&img[rel + 2], (double)(sc * dv.z));
+      atomicAdd(&img[rel + 3], (double)(sc * dv.w));
+    }
+  };
+  if (lpi == 8) {
+    // Z = 32: a pass of the workgroup takes 256 consecutive entries, one per thread, read with one
+    // coalesced load; the eight lanes that serve a chunk then get its entry from the lane that
+    // loaded it (lane u*8 + lane/8 of the same wave for the wave's u-th group of eight chunks).
+    const int lane = threadIdx.x & 63;
+    auto fetch_one = [&](uint32_t i) { return i < end ? lst[i] : make_uint2(0u, 0xffffffffu); };
+    uint2 nxt = fetch_one(first + threadIdx.x);
+    for (uint32_t i0 = first; i0 < end; i0 += 256) {       // uniform trip count for the workgroup
+      const uint2 mine = nxt;
+      uint2 e[U];
+      vfloat4 d[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int src = (u * 8 + (lane >> 3)) << 2;
+        e[u].x = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)mine.x);
+        e[u].y = (uint32_t)__builtin_amdgcn_ds_bpermute(src, (int)mine.y);
+        const uint32_t chunk = e[u].y != 0xffffffffu ? e[u].x : 0u;
+        d[u] = __builtin_nontemporal_load(reinterpret_cast<const vfloat4*>(dOut + (int64_t)chunk * a.Z) + sub);
+      }
+      nxt = fetch_one(i0 + 256 + threadIdx.x);
+#pragma unroll
+      for (int u = 0; u < U; ++u) add_chunk(e[u], d[u]);
+    }
+  } else {
   uint2 e[U], en[U];
   auto fetch_entries = [&](uint32_t i0, uint2* dst) {
 #pragma unroll
@@ -531,22 +571,8 @@ __global__ __launch_bounds__(256) void k_embed_accum(EmbedArgs a, int r_log2, ui
     }
     fetch_entries(i0 + U * ipp + which, en);
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const bool ok = e[u].y != 0xffffffffu;
-      const float sc = !ok ? 0.f : ((e[u].y & 0x80000000u) ? -a.lambda : a.lambda);
-      const int rel = (ok ? (int)((int64_t)(e[u].y & 0x7fffffffu) - slot0) : 0) + 4 * sub;
-      if constexpr (FIXED) {
-        atomicAdd(&img[rel + 0], to_fixed(sc * d[u].x, scale));
-        atomicAdd(&img[rel + 1], to_fixed(sc * d[u].y, scale));
-        atomicAdd(&img[rel + 2], to_fixed(sc * d[u].z, scale));
-        atomicAdd(&img[rel + 3], to_fixed(sc * d[u].w, scale));
-      } else {
-        atomicAdd(&img[rel + 0], (double)(sc * d[u].x));
-        atomicAdd(&img[rel + 1], (double)(sc * d[u].y));
-        atomicAdd(&img[rel + 2], (double)(sc * d[u].z));
-        atomicAdd(&img[rel + 3], (double)(sc * d[u].w));
-      }
-    }
+    for (int u = 0; u < U; ++u) add_chunk(e[u], d[u]);
+  }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < span; i += 256) {
