@@ -42,12 +42,17 @@ def parse():
     p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
     p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
     p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
-    p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg3_bert_stack_bf16", "cfg5_large_bf16",
+    p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg2_bert_ffn_bf16", "cfg3_bert_stack_bf16", "cfg5_large_bf16",
                                            "dim_sweep_b512"],
                    default="default",
                    help="default = the headline step (cfg2 ROAST-MM + cfg4 lookup); the others time forward, dX and "
                         "dM of every layer of another ROAST-MM configuration (a secondary figure, same JSON shape); "
                         "dim_sweep_b512 = square Dim x Dim layers at batch 512 with a dense bf16 GEMM beside each")
+    p.add_argument("--dtype", choices=["config", "f32"], default="config",
+                   help="cfg* workloads only: f32 runs the configuration's shapes with fp32 tensors (through the "
+                        "workspace entry points, i.e. on the matrix cores from bfloat16 planes)")
+    p.add_argument("--no-f32-workspace", action="store_true",
+                   help="fp32 workloads: call without workspaces (vector-ALU fp32 kernels)")
     p.add_argument("--dm-workspace", action="store_true",
                    help="atomic mode only: give roast_mm_bwd_dM its optional scratch (contraction parts x H x O "
                         "floats per call); about 7 %% faster dM, but a buffer of the size of the virtual weights, "
@@ -90,6 +95,9 @@ def time_optimizer(roast, torch, M, dM, Mb):
 def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     """Forward, dX and dM of every layer of one ROAST-MM configuration, all layers sharing M and dM."""
     cfg = wl.CONFIGS[args.workload]
+    if args.dtype == "f32":
+        import dataclasses
+        cfg = dataclasses.replace(cfg, dtype="f32")
     inp = wl.make_mm_inputs(cfg)
     bf16 = cfg.dtype == "bf16"
     M = to_dev(inp.M)
@@ -97,11 +105,15 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     dM = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
     layers = []
     tensors = {}
+    fill_rng = np.random.default_rng(cfg.seed + 1)
     for l in cfg.layers:
         d = roast.mm_desc(l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size, l.layer_id, cfg.lam, inp.hash)
         key = (l.H, l.O)
         if key not in tensors:      # one X / dY per distinct shape, reused by the layers of that shape
-            X, dY = to_dev(inp.X[l.name]), to_dev(inp.dY[l.name])
+            # a chained configuration draws only its first X and last dY: the rest is drawn here
+            Xn = inp.X[l.name] if l.name in inp.X else wl.draw_act(fill_rng, cfg.I, l.H, cfg.dtype)
+            dYn = inp.dY[l.name] if l.name in inp.dY else wl.draw_act(fill_rng, cfg.I, l.O, cfg.dtype)
+            X, dY = to_dev(Xn), to_dev(dYn)
             tensors[key] = (X, dY, torch.empty_like(dY), torch.empty_like(X))
         layers.append((d, l) + tensors[key])
     ws = None
@@ -109,13 +121,25 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
         ws = torch.empty(max(max(roast.roast_mm_bwd_dM_workspace(d, cfg.I, mode) for d, *_ in layers), 1),
                          dtype=torch.uint8, device="cuda")
 
+    wf = wx = None
+    if not bf16 and not args.no_f32_workspace:
+        # fp32: the workspaces with which the three products run on the matrix cores
+        nbytes = lambda f: max(max(f(d) for d, *_ in layers), 16)
+        wf = torch.empty(nbytes(lambda d: roast.roast_mm_fwd_workspace(d, torch.float32, cfg.I)), dtype=torch.uint8,
+                         device="cuda")
+        wx = torch.empty(nbytes(lambda d: roast.roast_mm_bwd_dx_workspace(d, torch.float32, cfg.I)), dtype=torch.uint8,
+                         device="cuda")
+        if mode == roast.ROAST_REDUCE_ATOMIC:
+            ws = torch.empty(nbytes(lambda d: roast.roast_mm_bwd_dM_workspace_f32(d, cfg.I)), dtype=torch.uint8,
+                             device="cuda")
+
     def step():
         if bf16:
             roast.roast_m_shadow_bf16(M, Mb)
         for d, l, X, dY, Y, dX in layers:
-            roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb)
+            roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb, ws=wf)
         for d, l, X, dY, Y, dX in reversed(layers):
-            roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb)
+            roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb, ws=wx)
             roast.roast_mm_bwd_dM(d, X, dY, dM, mode, ws)
 
     for _ in range(args.warmup):
@@ -138,7 +162,8 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32",
             "data": "synthetic", "pct_mfma_peak": 100.0 * tflops / peak,
             "config": {"workload": f"{cfg.name}: I={cfg.I}, {len(cfg.layers)} layer call(s), {cfg.Z1}x{cfg.Z2} tiles, "
-                                   f"|M|={cfg.m_size}", "reduce": args.reduce, "dm_workspace": ws is not None},
+                                   f"|M|={cfg.m_size}, {cfg.dtype}", "reduce": args.reduce, "dm_workspace": ws is not None,
+                       "f32_on_matrix_cores": wf is not None},
             "roofline": {"kernel": "whole step (all MM kernels)", "bound": "mfma" if bf16 else "alu", "achieved": tflops,
                          "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None}}
 

@@ -149,12 +149,17 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
                              const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream);
 
 /*
- * Small-batch variants of the two products above (Section 3.2's blocked product; the paper's
- * square-weight timings use batch 512).  With few rows the output has too few tiles to fill the
- * chip, so the contraction axis is split over workgroups: each writes an fp32 partial output to
- * the workspace and a second pass sums the parts in a fixed order and rounds once to `dt`.
- * The *_workspace queries return the bytes that help for these sizes (0: the plain call is used,
- * e.g. fp32, large I, or a shape the bf16 kernels do not cover).
+ * Workspace variants of the two products above.  What the workspace buys depends on `dt`:
+ *  - bf16, small batch (Section 3.2's blocked product; the paper's square-weight timings use batch
+ *    512): with few rows the output has too few tiles to fill the chip, so the contraction axis is
+ *    split over workgroups; each writes an fp32 partial output to the workspace and a second pass
+ *    sums the parts in a fixed order and rounds once to bf16.
+ *  - fp32: the product runs on the bf16 matrix cores.  X (or dY) and M are each held in the
+ *    workspace as three bfloat16 planes with x = hi + mid + lo exactly, and the six plane products of
+ *    weight >= 2^-16 are accumulated in fp32; what is dropped is below 2^-23 of |x||w| per term,
+ *    inside the fp32 bar of the conventions above.  Without a workspace fp32 runs on the vector ALUs.
+ * The *_workspace queries return the bytes that help for these sizes (0: nothing to gain, or a
+ * shape the matrix-core kernels do not cover; the plain call is used).
  * workspace: NULL (same as the plain call), or a DEVICE buffer, 16-byte aligned, of at least the
  * queried size (else ROAST_ERR_WORKSPACE); its contents are scratch, owned by the caller, and may be
  * reused by the next call on the same stream.  Results are deterministic for a fixed shape.
@@ -173,6 +178,9 @@ roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t 
  * workgroups) the per-split products are summed in the workspace and scattered with one atomic per
  * virtual weight; without it every split adds straight into dM. */
 size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode);
+/* fp32, ATOMIC mode only: bytes of the optional workspace with which roast_mm_bwd_dM runs the product
+ * on the matrix cores from bfloat16 planes of X and dY (see roast_mm_fwd_ws); 0 = shape not covered. */
+size_t roast_mm_bwd_dM_workspace_f32(const roast_mm_desc* d, int64_t I);
 
 /*
  * Gradient w.r.t. the shared array (Section 3.3 gradient equation, Appendix A.1):

@@ -20,7 +20,7 @@ ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
            "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx",
            "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
-           "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM",
+           "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd",
            "roast_embed_bag_fwd", "roast_embed_bag_bwd_workspace", "roast_embed_bag_bwd", "roast_optim_step"]
 
@@ -87,6 +87,8 @@ def load() -> C.CDLL:
     lib.roast_mm_bwd_dx_ws.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
     lib.roast_mm_bwd_dM_workspace.argtypes = [MP, i64, i32]
     lib.roast_mm_bwd_dM_workspace.restype = sz
+    lib.roast_mm_bwd_dM_workspace_f32.argtypes = [MP, i64]
+    lib.roast_mm_bwd_dM_workspace_f32.restype = sz
     lib.roast_mm_bwd_dM.argtypes = [MP, i32, i64, vp, i64, vp, i64, vp, i32, vp, sz, vp]
     lib.roast_embed_fwd.argtypes = [EP, i64, vp, vp, vp, vp, vp]
     lib.roast_embed_bwd_workspace.argtypes = [EP, i64, i32]
@@ -101,7 +103,7 @@ def load() -> C.CDLL:
         f = getattr(lib, name)
         if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
                         "roast_embed_bwd_workspace", "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace",
-                        "roast_embed_bag_bwd_workspace"):
+                        "roast_embed_bag_bwd_workspace", "roast_mm_bwd_dM_workspace_f32"):
             f.restype = i32
     _lib = lib
     return lib
@@ -283,6 +285,10 @@ def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None,
 
 def roast_mm_bwd_dM_workspace(desc: RoastMMDesc, I: int, mode: int = ROAST_REDUCE_ATOMIC) -> int:
     return int(load().roast_mm_bwd_dM_workspace(C.byref(desc), int(I), int(mode)))
+
+
+def roast_mm_bwd_dM_workspace_f32(desc: RoastMMDesc, I: int) -> int:
+    return int(load().roast_mm_bwd_dM_workspace_f32(C.byref(desc), int(I)))
 
 
 def roast_mm_bwd_dM(desc: RoastMMDesc, X, dY, dM, mode: int = ROAST_REDUCE_ATOMIC, ws=None, stream=None):

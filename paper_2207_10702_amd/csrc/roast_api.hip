@@ -113,14 +113,16 @@ roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, v
 
 size_t roast_mm_fwd_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I) {
   MMArgs a;
-  if (make_mm_args(d, I, &a) != ROAST_OK || dt != ROAST_BF16 || I == 0) return 0;
+  if (make_mm_args(d, I, &a) != ROAST_OK || !dtype_ok(dt) || I == 0) return 0;
+  if (dt == ROAST_F32) return x3_fwd_workspace(a);
   const int s = mfma_fwd_splits(a);
   return s > 1 ? (size_t)s * (size_t)I * (size_t)a.O * sizeof(float) : 0;
 }
 
 size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I) {
   MMArgs a;
-  if (make_mm_args(d, I, &a) != ROAST_OK || dt != ROAST_BF16 || I == 0) return 0;
+  if (make_mm_args(d, I, &a) != ROAST_OK || !dtype_ok(dt) || I == 0) return 0;
+  if (dt == ROAST_F32) return x3_dx_workspace(a);
   const int s = mfma_dx_splits(a);
   return s > 1 ? (size_t)s * (size_t)I * (size_t)a.H * sizeof(float) : 0;
 }
@@ -139,6 +141,13 @@ roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
     if (workspace && (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0)) return ROAST_ERR_WORKSPACE;
     st = mfma_mm_fwd(a, X, ldx, M, M_bf16, Y, ldy, need ? (float*)workspace : nullptr, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
+  } else if (workspace) {
+    const size_t need = roast_mm_fwd_workspace(d, dt, I);
+    if (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0) return ROAST_ERR_WORKSPACE;
+    if (need) {
+      st = x3_mm_fwd(a, (const float*)X, ldx, M, (float*)Y, ldy, workspace, (hipStream_t)stream);
+      if (st != ROAST_ERR_UNSUPPORTED) return st;
+    }
   }
   return generic_mm_fwd(a, dt, X, ldx, M, Y, ldy, (hipStream_t)stream);
 }
@@ -162,6 +171,13 @@ roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t 
     if (workspace && (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0)) return ROAST_ERR_WORKSPACE;
     st = mfma_mm_bwd_dx(a, dY, ldy, M, M_bf16, dX, ldx, need ? (float*)workspace : nullptr, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
+  } else if (workspace) {
+    const size_t need = roast_mm_bwd_dx_workspace(d, dt, I);
+    if (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0) return ROAST_ERR_WORKSPACE;
+    if (need) {
+      st = x3_mm_bwd_dx(a, (const float*)dY, ldy, M, (float*)dX, ldx, workspace, (hipStream_t)stream);
+      if (st != ROAST_ERR_UNSUPPORTED) return st;
+    }
   }
   return generic_mm_bwd_dx(a, dt, dY, ldy, M, dX, ldx, (hipStream_t)stream);
 }
@@ -169,6 +185,12 @@ roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t 
 roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
                              const float* M, const void* M_bf16, void* dX, int64_t ldx, void* stream) {
   return roast_mm_bwd_dx_ws(d, dt, I, dY, ldy, M, M_bf16, dX, ldx, nullptr, 0, stream);
+}
+
+size_t roast_mm_bwd_dM_workspace_f32(const roast_mm_desc* d, int64_t I) {
+  MMArgs a;
+  if (make_mm_args(d, I, &a) != ROAST_OK || I == 0) return 0;
+  return x3_dm_workspace(a);
 }
 
 size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce_mode mode) {
@@ -202,6 +224,13 @@ roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
     }
     st = mfma_mm_bwd_dM(a, X, ldx, dY, ldy, dM, nullptr, 0, (hipStream_t)stream);
     if (st != ROAST_ERR_UNSUPPORTED) return st;
+  } else {
+    // optional workspace: the product runs on the matrix cores from bfloat16 planes of X and dY
+    const size_t want = x3_dm_workspace(a);
+    if (want && ws && ws_bytes >= want && ((uintptr_t)ws & 15) == 0) {
+      st = x3_mm_bwd_dM(a, (const float*)X, ldx, (const float*)dY, ldy, dM, ws, (hipStream_t)stream);
+      if (st != ROAST_ERR_UNSUPPORTED) return st;
+    }
   }
   return generic_mm_bwd_dM_atomic(a, dt, X, ldx, dY, ldy, dM, (hipStream_t)stream);
 }

@@ -113,6 +113,17 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
                          int64_t ldy, float* ws, hipStream_t s);
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
                             void* dX, int64_t ldx, float* ws, hipStream_t s);
+// fp32 operands on the bf16 matrix cores (three bfloat16 planes per operand, six plane products):
+// workspace bytes (0: shape not covered) and the three products; UNSUPPORTED -> generic kernels.
+size_t x3_fwd_workspace(const MMArgs& a);
+size_t x3_dx_workspace(const MMArgs& a);
+size_t x3_dm_workspace(const MMArgs& a);
+roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, float* Y, int64_t ldy, void* ws,
+                       hipStream_t s);
+roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, float* dX, int64_t ldx,
+                          void* ws, hipStream_t s);
+roast_status x3_mm_bwd_dM(const MMArgs& a, const float* X, int64_t ldx, const float* dY, int64_t ldy, float* dM,
+                          void* ws, hipStream_t s);
 // Gws == nullptr: atomically add lambda*sign*G into dM.  Gws != nullptr: store raw per-split G there
 // ([splits][H][O] floats) for the deterministic reduction; `splits` must equal dm_det_splits().
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,

@@ -91,6 +91,10 @@ struct KernArgs {
   int64_t mb_stride;
   uint16_t* C;         // FWD: Y, DX: dX
   int64_t ldc;
+  // X3 kernels (fp32 operands split into three bfloat16 planes): element distance between the planes
+  // of A, of B (dM only) and of the shadow of M, and the fp32 output of FWD / DX (row stride ldc)
+  int64_t a_plane, b_plane, mb_plane;
+  float* C32;
   float* dM;           // DM, atomic mode
   float* G;            // DM, deterministic mode: raw products [split][H][O]
                        // FWD / DX with a split contraction: fp32 partial outputs [split][I][columns]
@@ -194,8 +198,14 @@ struct RegSet {
 };
 
 
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
+// X3: fp32 in, fp32 out on the bf16 matrix cores.  Every fp32 operand value x is held as three
+// bfloat16 planes with x = hi + mid + lo exactly (3 x 8 significand bits); a product x*w is the sum
+// of nine plane products, of which the six of weight >= 2^-16 are kept: (hi,hi) (hi,mid) (mid,hi)
+// (hi,lo) (lo,hi) (mid,mid).  What is dropped is below 2^-23 of |x||w|, the accumulation is the
+// usual fp32 one.  The contraction loop simply runs six times as many steps: step = 6*kq + pair.
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false>
 __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p) {
+  static_assert(!X3 || SHADOW || MODE == MODE_DM, "the plane kernels read the weight planes, not fp32 M");
   constexpr int NC = WGM * WGN;                  // consumer waves
   // Eight producer waves follow the consumers: waves NC..NC+3 bring in the A operand (forward / dX:
   // direct-to-LDS loads of the activations; dM: X transposed through registers), waves NC+4..NC+7
@@ -239,7 +249,11 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     k_begin = bz * p.rows_per_split;
     k_end = min(k_end, k_begin + p.rows_per_split);
   }
-  const int nsteps = max(0, (k_end - k_begin + BK - 1) / BK);   // identical for every wave of the workgroup
+  const int nsteps_k = max(0, (k_end - k_begin + BK - 1) / BK);
+  const int nsteps = X3 ? 6 * nsteps_k : nsteps_k;               // identical for every wave of the workgroup
+  auto step_k0 = [&](int step) { return k_begin + (X3 ? step / 6 : step) * BK; };
+  auto step_asel = [&](int step) { return X3 ? (0x120100 >> (4 * (step % 6))) & 3 : 0; };   // plane of A
+  auto step_bsel = [&](int step) { return X3 ? (0x102010 >> (4 * (step % 6))) & 3 : 0; };   // plane of B / M
 
   // ---- tile table (all threads)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
@@ -303,7 +317,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     // that the in-order wait counts below are the same in every iteration.
     auto dma_issue = [&](int step) {
       if constexpr (ADMA) {
-        const int k0 = k_begin + min(step, nsteps - 1) * BK;
+        const int st = min(step, nsteps - 1);
+        const int64_t k0 = step_k0(st) + (X3 ? step_asel(st) * p.a_plane : 0);
         char* dst = a_stage(step) + (wave - NC) * (BM / 4) * 128;
 #pragma unroll
         for (int q = 0; q < Ctx::A_LOADS; ++q)
@@ -334,7 +349,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     }
 
     auto load_global = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
-      const int k0 = k_begin + step * BK;
+      const int k0 = step_k0(step);
+      [[maybe_unused]] const uint16_t* Mb = X3 ? p.Mb + step_bsel(step) * p.mb_plane : p.Mb;
       // Keep the issue order of the load groups the same everywhere (prologue and loop): the wait
       // counters are in-order, and a differing order would make the waits before the LDS writes
       // cover the newest loads as well.
@@ -344,7 +360,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         const int64_t off0 = s_off[e];
         const int64_t rel = off0 + (int64_t)a.Z2 * (k0 % a.Z1 + 4 * (pt / Ctx::FS_NG)) + c.fs_nin;
         // everything added to the tile base is even (Z2 % 8 == 0): the base's parity picks the copy
-        const uint16_t* mb = p.Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);
+        const uint16_t* mb = Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);
         r.fw_sgn = s_sgn[e];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -369,7 +385,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
           const int64_t off0 = s_off[e];
-          const uint16_t* mb = p.Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);   // row offsets are even (Z2 % 8 == 0)
+          const uint16_t* mb = Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);     // row offsets are even (Z2 % 8 == 0)
           const h8a m = *reinterpret_cast<const h8a*>(mb + off0 + c.dx_rowoff[q] + kin);
           r.ds_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
           r.dx_sgn[q] = s_sgn[e];
@@ -451,9 +467,13 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       auto dm_loop = [&](auto* loader_type, const uint16_t* src, int64_t ld, int col, bool is_a) {
         using TL = typename std::remove_pointer<decltype(loader_type)>::type;
         TL rs[NSETS];
-        auto fetch = [&](TL& r, int step) { r.load(src, ld, k_begin + step * BK, I - 1, col, pt >> 5); };
+        const int64_t plane = is_a ? p.a_plane : p.b_plane;
+        auto fetch = [&](TL& r, int step) {
+          const uint16_t* from = X3 ? src + (is_a ? step_asel(step) : step_bsel(step)) * plane : src;
+          r.load(from, ld, step_k0(step), I - 1, col, pt >> 5);
+        };
         auto stage = [&](TL& r, int step) {
-          r.store(is_a ? a_stage(step) : b_stage(step), k_begin + step * BK, k_end, pt & 31, pt >> 5);
+          r.store(is_a ? a_stage(step) : b_stage(step), step_k0(step), k_end, pt & 31, pt >> 5);
         };
         const int last = nsteps - 1;
         if (nsteps > 0) {
@@ -598,13 +618,15 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
     // Each wave stages one 32-row block at a time in its own LDS buffer and writes it out 16 bytes
     // per lane, row-contiguous.
-    if (p.G != nullptr) {
-      // split contraction: this workgroup's fp32 partial tile goes to its part of the workspace
+    if (X3 || p.G != nullptr) {
+      // fp32 out: the result itself (X3), or, with a split contraction, this workgroup's partial
+      // tile, which goes to its part of the workspace
       constexpr int ES = WTN * 4 + 16;          // bytes per staged row
       constexpr int CPR = WTN / 4, RPI = 64 / CPR;
       static_assert(NC * 32 * ES <= TILES_BYTES, "fp32 epilogue staging must fit in the operand stages");
       char* ebuf = smem + wave * (32 * ES);
-      float* part = p.G + (int64_t)bz * Mdim * Ndim;
+      float* part = p.G ? p.G + (int64_t)bz * Mdim * Ndim : p.C32;
+      const int64_t ldp = p.G ? (int64_t)Ndim : p.ldc;
 #pragma unroll
       for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -620,7 +642,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           const int r = it * RPI + lane / CPR, cc = lane % CPR;
           const float4v v = *reinterpret_cast<const float4v*>(ebuf + r * ES + cc * 16);
           const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 4;
-          if (row < Mdim && col < Ndim) *reinterpret_cast<float4v*>(part + (int64_t)row * Ndim + col) = v;
+          if (row < Mdim && col < Ndim) *reinterpret_cast<float4v*>(part + row * ldp + col) = v;
         }
       }
       return;
@@ -681,7 +703,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
 template <int MODE, int BM, int BN>
 constexpr int smem_bytes() { return ((MODE != MODE_DM ? 3 : 2) * BM + 2 * BN) * 128 + kMaxTable * 12; }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW>
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false>
 roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
@@ -691,12 +713,12 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   static_assert(smem <= 160 * 1024, "LDS budget");
   static bool configured = false;   // one attribute call per instantiation per process
   if (!configured) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
     configured = true;
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW>), grid, dim3((WGM * WGN + 8) * 64), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>), grid, dim3((WGM * WGN + 8) * 64), smem, s, p);
   return hip_status(hipGetLastError());
 }
 
@@ -729,13 +751,78 @@ __global__ __launch_bounds__(256) void k_split_finish(const float* __restrict__ 
   *reinterpret_cast<uint4v*>(C + r * ldc + c) = v;
 }
 
+// fp32 -> three bfloat16 values with x == hi + mid + lo exactly: each plane takes the leading 8
+// significand bits of what is left (truncation, so the partial sums hi, hi + mid, ... grow
+// monotonically towards x and cannot overflow).  Each residual is exact in fp32.  Below 2^-110 the
+// residuals become subnormal and lose their low bits (absolute error below 2^-133).  Inf / NaN stay
+// in the first plane (their products with the zero planes of the other operand are NaN).
+__device__ inline void split3(float x, uint16_t* hi, uint16_t* mid, uint16_t* lo) {
+  const uint32_t bits = __builtin_bit_cast(uint32_t, x);
+  if ((bits & 0x7f800000u) == 0x7f800000u) {
+    *hi = (uint16_t)((bits >> 16) | ((bits & 0xffffu) ? 0x40u : 0u));   // keep a NaN a NaN
+    *mid = *lo = 0;
+    return;
+  }
+  const uint32_t h = bits & 0xffff0000u;
+  const float r1 = x - __builtin_bit_cast(float, h);
+  const uint32_t m = __builtin_bit_cast(uint32_t, r1) & 0xffff0000u;
+  const float r2 = r1 - __builtin_bit_cast(float, m);
+  *hi = (uint16_t)(h >> 16);
+  *mid = (uint16_t)(m >> 16);
+  *lo = (uint16_t)(__builtin_bit_cast(uint32_t, r2) >> 16);
+}
+
+// planes[s][r * ldo + c] = plane s of src[r * ld + c]
+__global__ __launch_bounds__(256) void k_split3_rows(const float* __restrict__ src, int64_t rows, int64_t cols,
+                                                     int64_t ld, uint16_t* __restrict__ out, int64_t ldo,
+                                                     int64_t plane) {
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= rows * cols) return;
+  const int64_t r = t / cols, c = t - r * cols;
+  uint16_t h, m, l;
+  split3(src[r * ld + c], &h, &m, &l);
+  uint16_t* o = out + r * ldo + c;
+  o[0] = h;
+  o[plane] = m;
+  o[2 * plane] = l;
+}
+
+// Three shadows of M, one per plane, each in the two-copy layout of k_shadow_bf16:
+// out[s * 2 * stride + i] = plane s of M[i], out[s * 2 * stride + stride + i] = plane s of M[i + 1]
+__global__ __launch_bounds__(256) void k_shadow3(const float* __restrict__ M, int64_t n, int64_t stride,
+                                                 uint16_t* __restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= stride) return;
+  uint16_t c[3] = {0, 0, 0}, x[3] = {0, 0, 0};
+  if (i < n) split3(M[i], &c[0], &c[1], &c[2]);
+  if (i + 1 < n) split3(M[i + 1], &x[0], &x[1], &x[2]);
+#pragma unroll
+  for (int s = 0; s < 3; ++s) {
+    out[(int64_t)s * 2 * stride + i] = c[s];
+    out[(int64_t)s * 2 * stride + stride + i] = x[s];
+  }
+}
+
+// fp32 result of a split contraction: C[r][c] = sum over the parts, in order, of G[part][r][c]
+__global__ __launch_bounds__(256) void k_split_finish_f32(const float* __restrict__ G, int parts, int64_t rows,
+                                                          int64_t cols, float* __restrict__ C, int64_t ldc) {
+  const int64_t cpr = cols / 4;
+  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (t >= rows * cpr) return;
+  const int64_t r = t / cpr, c = (t % cpr) * 4;
+  float4v sum = {0.f, 0.f, 0.f, 0.f};
+  for (int q = 0; q < parts; ++q) sum += *reinterpret_cast<const float4v*>(G + ((int64_t)q * rows + r) * cols + c);
+  *reinterpret_cast<float4v*>(C + r * ldc + c) = sum;
+}
+
+inline int64_t shadow_stride_of(int64_t m_size) { return (m_size + 1 + 63) / 64 * 64; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 }  // namespace
 
 
-int64_t shadow_stride(int64_t m_size) { return (m_size + 1 + 63) / 64 * 64; }
+int64_t shadow_stride(int64_t m_size) { return shadow_stride_of(m_size); }
 
 roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hipStream_t s) {
   const int64_t stride = shadow_stride(m_size);
@@ -757,9 +844,34 @@ void split_setup(KernArgs* p, dim3* grid, int64_t K, int splits, float* ws) {
 
 roast_status split_finish(const KernArgs& p, unsigned parts, int64_t rows, int64_t cols, hipStream_t s) {
   if (p.G == nullptr) return ROAST_OK;
-  const int64_t blocks = cdiv(rows * (cols / 8), 256);
+  const int64_t blocks = cdiv(rows * (cols / (p.C32 ? 4 : 8)), 256);
   if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(k_split_finish, dim3((unsigned)blocks), dim3(256), 0, s, p.G, (int)parts, rows, cols, p.C, p.ldc);
+  if (p.C32)
+    hipLaunchKernelGGL(k_split_finish_f32, dim3((unsigned)blocks), dim3(256), 0, s, p.G, (int)parts, rows, cols, p.C32,
+                       p.ldc);
+  else
+    hipLaunchKernelGGL(k_split_finish, dim3((unsigned)blocks), dim3(256), 0, s, p.G, (int)parts, rows, cols, p.C, p.ldc);
+  return hip_status(hipGetLastError());
+}
+
+inline size_t up256(size_t v) { return (v + 255) / 256 * 256; }
+inline int64_t pad8(int64_t v) { return (v + 7) / 8 * 8; }
+
+// planes of a rows x cols fp32 matrix: 3 x rows x pad8(cols) bfloat16
+size_t planes_bytes(int64_t rows, int64_t cols) { return up256((size_t)3 * rows * pad8(cols) * 2); }
+size_t shadow3_bytes(int64_t m_size) { return up256((size_t)3 * 2 * shadow_stride_of(m_size) * 2); }
+
+roast_status split_rows(const float* src, int64_t rows, int64_t cols, int64_t ld, uint16_t* out, hipStream_t s) {
+  const int64_t blocks = cdiv(rows * cols, 256);
+  if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(k_split3_rows, dim3((unsigned)blocks), dim3(256), 0, s, src, rows, cols, ld, out, pad8(cols),
+                     rows * pad8(cols));
+  return hip_status(hipGetLastError());
+}
+
+roast_status shadow3(const float* M, int64_t m_size, uint16_t* out, hipStream_t s) {
+  const int64_t stride = shadow_stride_of(m_size);
+  hipLaunchKernelGGL(k_shadow3, dim3((unsigned)cdiv(stride, 256)), dim3(256), 0, s, M, m_size, stride, out);
   return hip_status(hipGetLastError());
 }
 
@@ -828,6 +940,95 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   p.rows_per_split = (int)rows;
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
   return launch<MODE_DM, BM, BN, 4, 2, false>(p, grid, s);
+}
+
+// ---- fp32 through the three-plane kernels.  Workspace layout (every part 256-byte aligned):
+// forward: [planes of X][three shadows of M][partial outputs of a split contraction]
+// dX     : [planes of dY][three shadows of M][partial outputs]
+// dM     : [planes of X][planes of dY]
+bool x3_fwd_ok(const MMArgs& a) { return mfma_fwd_ok(a) && a.Z2 % 8 == 0 && a.O % 4 == 0; }
+bool x3_dx_ok(const MMArgs& a) { return mfma_dx_ok(a) && a.H % 4 == 0; }
+bool x3_dm_ok(const MMArgs& a) {
+  return a.Z1 % 32 == 0 && a.Z2 % 32 == 0 && a.H % 8 == 0 && a.O % 8 == 0 && a.H >= kBM / 32 && a.O >= kBN / 32 &&
+         (cdiv(kBM, a.Z1) + 1) * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
+}
+int x3_fwd_splits(const MMArgs& a) { return mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), 6 * a.H); }
+int x3_dx_splits(const MMArgs& a) { return mm_pick_splits(cdiv(a.H, kBN) * cdiv(a.I, kBM), 6 * a.O); }
+
+size_t x3_fwd_workspace(const MMArgs& a) {
+  if (!x3_fwd_ok(a)) return 0;
+  const int s = x3_fwd_splits(a);
+  return planes_bytes(a.I, a.H) + shadow3_bytes(a.m_size) + (s > 1 ? (size_t)s * a.I * a.O * 4 : 0);
+}
+size_t x3_dx_workspace(const MMArgs& a) {
+  if (!x3_dx_ok(a)) return 0;
+  const int s = x3_dx_splits(a);
+  return planes_bytes(a.I, a.O) + shadow3_bytes(a.m_size) + (s > 1 ? (size_t)s * a.I * a.H * 4 : 0);
+}
+size_t x3_dm_workspace(const MMArgs& a) {
+  return x3_dm_ok(a) ? planes_bytes(a.I, a.H) + planes_bytes(a.I, a.O) : 0;
+}
+
+roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, float* Y, int64_t ldy, void* ws,
+                       hipStream_t s) {
+  if (!x3_fwd_ok(a) || ldy % 4 != 0 || !aligned16(Y) || !aligned16(ws)) return ROAST_ERR_UNSUPPORTED;
+  char* base = (char*)ws;
+  uint16_t* Xp = (uint16_t*)base;
+  uint16_t* Mp = (uint16_t*)(base + planes_bytes(a.I, a.H));
+  float* parts = (float*)(base + planes_bytes(a.I, a.H) + shadow3_bytes(a.m_size));
+  roast_status st = split_rows(X, a.I, a.H, ldx, Xp, s);
+  if (st != ROAST_OK) return st;
+  st = shadow3(M, a.m_size, Mp, s);
+  if (st != ROAST_OK) return st;
+  KernArgs p{};
+  p.a = a; p.A = Xp; p.lda = pad8(a.H); p.a_plane = a.I * pad8(a.H); p.M = M; p.Mb = Mp;
+  p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = Y; p.ldc = ldy;
+  dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.I, kBM), 1);
+  split_setup(&p, &grid, a.H, x3_fwd_splits(a), parts);
+  st = launch<MODE_FWD, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
+}
+
+roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, float* dX, int64_t ldx,
+                          void* ws, hipStream_t s) {
+  if (!x3_dx_ok(a) || ldx % 4 != 0 || !aligned16(dX) || !aligned16(ws)) return ROAST_ERR_UNSUPPORTED;
+  char* base = (char*)ws;
+  uint16_t* Gp = (uint16_t*)base;
+  uint16_t* Mp = (uint16_t*)(base + planes_bytes(a.I, a.O));
+  float* parts = (float*)(base + planes_bytes(a.I, a.O) + shadow3_bytes(a.m_size));
+  roast_status st = split_rows(dY, a.I, a.O, ldy, Gp, s);
+  if (st != ROAST_OK) return st;
+  st = shadow3(M, a.m_size, Mp, s);
+  if (st != ROAST_OK) return st;
+  KernArgs p{};
+  p.a = a; p.A = Gp; p.lda = pad8(a.O); p.a_plane = a.I * pad8(a.O); p.M = M; p.Mb = Mp;
+  p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = dX; p.ldc = ldx;
+  dim3 grid((unsigned)cdiv(a.H, kBN), (unsigned)cdiv(a.I, kBM), 1);
+  split_setup(&p, &grid, a.O, x3_dx_splits(a), parts);
+  st = launch<MODE_DX, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
+}
+
+roast_status x3_mm_bwd_dM(const MMArgs& a, const float* X, int64_t ldx, const float* dY, int64_t ldy, float* dM,
+                          void* ws, hipStream_t s) {
+  if (!x3_dm_ok(a) || !aligned16(ws)) return ROAST_ERR_UNSUPPORTED;
+  char* base = (char*)ws;
+  uint16_t* Xp = (uint16_t*)base;
+  uint16_t* Gp = (uint16_t*)(base + planes_bytes(a.I, a.H));
+  roast_status st = split_rows(X, a.I, a.H, ldx, Xp, s);
+  if (st != ROAST_OK) return st;
+  st = split_rows(dY, a.I, a.O, ldy, Gp, s);
+  if (st != ROAST_OK) return st;
+  const int64_t tiles = cdiv(a.H, kBM) * cdiv(a.O, kBN);
+  const int splits = dm_pick_splits(tiles, 6 * a.I);
+  int64_t rows = cdiv(a.I, splits);
+  rows = cdiv(rows, BK) * BK;
+  KernArgs p{};
+  p.a = a; p.A = Xp; p.lda = pad8(a.H); p.a_plane = a.I * pad8(a.H);
+  p.B = Gp; p.ldb = pad8(a.O); p.b_plane = a.I * pad8(a.O); p.dM = dM;
+  p.rows_per_split = (int)rows;
+  const dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.H, kBM), (unsigned)cdiv(a.I, rows));
+  return launch<MODE_DM, kBM, kBN, 4, 2, false, true>(p, grid, s);
 }
 
 }  // namespace roast

@@ -245,3 +245,38 @@ def test_cfg5_large_bf16_full_size(roast):
         got = to_host_f64(got_all[j0:j0 + 256])
         err = np.max(np.abs(got - ref) / np.maximum(np.abs(ref), rms))
         assert err <= BF16_TOL, (j0, err)
+
+
+# ------------------------------------------------------------------ config 2's shapes in fp32 (matrix-core plane kernels)
+def test_cfg2_shapes_fp32_on_matrix_cores_full_size(roast):
+    import dataclasses
+    cfg = dataclasses.replace(wl.CONFIGS["cfg2_bert_ffn_bf16"], dtype="f32", chained=False)
+    inp = wl.make_mm_inputs(cfg)
+    rng = np.random.default_rng(22)
+    h, lam = inp.hash, float(np.float32(cfg.lam))
+    Md = to_dev(inp.M)
+    for l in cfg.layers:
+        d = roast.mm_desc(l.H, l.O, cfg.Z1, cfg.Z2, cfg.m_size, l.layer_id, cfg.lam, h)
+        Xd, dYd = to_dev(inp.X[l.name]), to_dev(inp.dY[l.name])
+        sizes = (roast.roast_mm_fwd_workspace(d, torch.float32, cfg.I), roast.roast_mm_bwd_dx_workspace(d, torch.float32, cfg.I),
+                 roast.roast_mm_bwd_dM_workspace_f32(d, cfg.I))
+        assert min(sizes) > 0
+        ws = torch.empty(max(sizes), dtype=torch.uint8, device="cuda")
+        Y = roast.roast_mm_fwd(d, Xd, Md, ws=ws)
+        dX = roast.roast_mm_bwd_dx(d, dYd, Md, ws=ws)
+        dM = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
+        roast.roast_mm_bwd_dM(d, Xd, dYd, dM, roast.ROAST_REDUCE_ATOMIC, ws)
+        torch.cuda.synchronize()
+        check_layer_sampled(roast, cfg, l, h, inp.M, Md, Xd, dYd, Y, dX, rng, 64, F32_TOL)
+        Xo, dYo = to_host_f64(Xd), to_host_f64(dYd)
+        got = to_host_f64(dM)
+        rms = float(np.sqrt(np.mean(got * got)))
+        for j0 in np.concatenate([[0, cfg.m_size - 48], rng.choice(cfg.m_size - 48, size=4, replace=False)]):
+            ref = oracle.dm_window(h, l.layer_id, cfg.Z1, cfg.Z2, cfg.m_size, lam, Xo, dYo, int(j0), int(j0) + 48)
+            err = np.max(np.abs(got[j0:j0 + 48] - ref) / np.maximum(np.abs(ref), rms))
+            assert err <= F32_TOL, (l.name, int(j0), err)
+        # fp32 outputs: the adjoint identities hold to fp32 accuracy on the complete tensors
+        s_y, n_y = dot_scale(dYd, Y)
+        s_x, _ = dot_scale(dX, Xd)
+        s_m, _ = dot_scale(dM, Md)
+        assert abs(s_y - s_x) <= 1e-4 * n_y and abs(s_y - s_m) <= 1e-4 * n_y, (l.name, s_y, s_x, s_m, n_y)
