@@ -101,7 +101,7 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     inp = wl.make_mm_inputs(cfg)
     bf16 = cfg.dtype == "bf16"
     M = to_dev(inp.M)
-    Mb = roast.roast_m_shadow_bf16(M) if bf16 else None
+    Mb = roast.roast_m_shadow_bf16(M) if bf16 else (None if args.no_f32_workspace else roast.roast_m_planes_bf16(M))
     dM = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
     layers = []
     tensors = {}
@@ -136,6 +136,8 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     def step():
         if bf16:
             roast.roast_m_shadow_bf16(M, Mb)
+        elif Mb is not None:
+            roast.roast_m_planes_bf16(M, Mb)
         for d, l, X, dY, Y, dX in layers:
             roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb, ws=wf)
         for d, l, X, dY, Y, dX in reversed(layers):
@@ -174,6 +176,8 @@ def bench_dim_sweep(args, roast, wl, torch, np):
     step, each timed alone, with the vendor dense bf16 GEMM of the same shape beside them.  The
     printed Dim 8096 is run as 8192 (a multiple of the tile)."""
     I, Z = 512, 64
+    f32 = args.dtype == "f32"
+    tdt = torch.float32 if f32 else torch.bfloat16
     dims = [512, 1024, 2048, 4096, 8192, 10240, 20480]
     m_sizes = [1 << 20, 16 << 20, 128 << 20]
     g = torch.Generator(device="cuda").manual_seed(2207)
@@ -192,14 +196,15 @@ def bench_dim_sweep(args, roast, wl, torch, np):
 
     rows = []
     Ms = {m: torch.randn(m, dtype=torch.float32, device="cuda", generator=g) * 0.02 for m in m_sizes}
-    shadows = {m: roast.roast_m_shadow_bf16(Ms[m]) for m in m_sizes}
+    # made once per M, as after an optimizer step: the bf16 shadow, or for fp32 the three bfloat16 planes
+    shadows = {m: (roast.roast_m_planes_bf16(Ms[m]) if f32 else roast.roast_m_shadow_bf16(Ms[m])) for m in m_sizes}
     dM = torch.zeros(max(m_sizes), dtype=torch.float32, device="cuda")
     for dim in dims:
         reps = max(5, min(args.steps, int(4e6 / dim)))
-        X = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
-        dY = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(torch.bfloat16)
+        X = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(tdt)
+        dY = torch.randn((I, dim), dtype=torch.float32, device="cuda", generator=g).to(tdt)
         Y, dX = torch.empty_like(X), torch.empty_like(X)
-        W = (torch.randn((dim, dim), dtype=torch.float32, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+        W = (torch.randn((dim, dim), dtype=torch.float32, device="cuda", generator=g) * 0.02).to(tdt)
         dW = torch.empty_like(W)
         row = {"Dim": dim, "GFLOP_per_product": 2.0 * I * dim * dim / 1e9,
                "dense_fwd_ms": timed(lambda: torch.matmul(X, W, out=Y), reps),
@@ -208,14 +213,15 @@ def bench_dim_sweep(args, roast, wl, torch, np):
         del W, dW
         for m in m_sizes:
             d = roast.mm_desc(dim, dim, Z, Z, m, 0, 1.0, hp)
-            nbytes = max(roast.roast_mm_fwd_workspace(d, torch.bfloat16, I),
-                         roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, I), 16)
+            nbytes = max(roast.roast_mm_fwd_workspace(d, tdt, I), roast.roast_mm_bwd_dx_workspace(d, tdt, I),
+                         roast.roast_mm_bwd_dM_workspace_f32(d, I) if f32 else 0, 16)
             ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             M, Mb, dMv = Ms[m], shadows[m], dM[:m]
+            wsm = ws if f32 else None
             r = {"fwd_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb, ws=ws), reps),
                  "fwd_no_ws_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y, M_bf16=Mb), reps),
                  "dx_ms": timed(lambda: roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb, ws=ws), reps),
-                 "dM_ms": timed(lambda: roast.roast_mm_bwd_dM(d, X, dY, dMv, roast.ROAST_REDUCE_ATOMIC), reps),
+                 "dM_ms": timed(lambda: roast.roast_mm_bwd_dM(d, X, dY, dMv, roast.ROAST_REDUCE_ATOMIC, wsm), reps),
                  "workspace_MB": nbytes / 1e6}
             row["roast"][f"{m * 4 >> 20}MB"] = r
             del ws
@@ -240,8 +246,9 @@ def bench_dim_sweep(args, roast, wl, torch, np):
     avg = lambda key, m: sum(r["roast"][m][key] for r in rows) / len(rows)
     return {"metric": "ROAST-MM forward TFLOP/s at Dim 20480, batch 512, |M| 4 MB", "unit": "TFLOP/s", "value": tflops,
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best, "higher_is_better": True,
-            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": "dim_sweep_b512: square Dim x Dim, batch 512, 64x64 tiles, |M| 4 / 64 / 512 MB"},
+            "scaling": "weak", "vs_baseline": None, "dtype": "f32" if f32 else "bf16", "data": "synthetic",
+            "config": {"workload": "dim_sweep_b512: square Dim x Dim, batch 512, 64x64 tiles, |M| 4 / 64 / 512 MB, "
+                                   + ("fp32 on the matrix cores (bfloat16 planes)" if f32 else "bf16")},
             "averages_ms": {m: {k: avg(k, m) for k in ("fwd_ms", "dx_ms", "dM_ms")} for m in last["roast"]},
             "dense_averages_ms": {k: sum(r[k] for r in rows) / len(rows)
                                   for k in ("dense_fwd_ms", "dense_dx_ms", "dense_dw_ms")},
@@ -249,7 +256,8 @@ def bench_dim_sweep(args, roast, wl, torch, np):
                                            / sum(r["roast"][m]["fwd_ms"] for r in rows) for m in ("4MB", "512MB")},
             "table": rows,
             "roofline": {"kernel": "roast_mm_fwd at Dim 20480", "bound": "mfma", "achieved": tflops,
-                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": tflops / PEAK_BF16_TFLOPS, "traffic": None}}
+                         "peak": 157.3 if f32 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tflops / (157.3 if f32 else PEAK_BF16_TFLOPS), "traffic": None}}
 
 
 def main():

@@ -164,6 +164,15 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
  * queried size (else ROAST_ERR_WORKSPACE); its contents are scratch, owned by the caller, and may be
  * reused by the next call on the same stream.  Results are deterministic for a fixed shape.
  */
+/*
+ * fp32 calls only: the three bfloat16 planes of M (each in the layout of the bf16 shadow), made once
+ * per update of M and passed as `M_bf16` to fp32 roast_mm_fwd_ws / roast_mm_bwd_dx_ws calls, which
+ * otherwise rebuild them in their workspace on every call (a pass over |M|).
+ * planes: DEVICE buffer of roast_m_planes_bytes(m_size) bytes, 16-byte aligned, owned by the caller.
+ */
+size_t roast_m_planes_bytes(int64_t m_size);
+roast_status roast_m_planes_bf16(const float* M, int64_t m_size, void* planes, void* stream);
+
 size_t roast_mm_fwd_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I);
 size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t I);
 roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,

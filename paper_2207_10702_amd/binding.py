@@ -18,7 +18,8 @@ ROAST_OK, ROAST_ERR_ARG, ROAST_ERR_SHAPE, ROAST_ERR_RANGE, ROAST_ERR_WORKSPACE, 
 ROAST_REDUCE_ATOMIC, ROAST_REDUCE_DETERMINISTIC = 0, 1
 
 EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device", "roast_chunk_index_device",
-           "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_mm_fwd", "roast_mm_bwd_dx",
+           "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_m_planes_bytes", "roast_m_planes_bf16",
+           "roast_mm_fwd", "roast_mm_bwd_dx",
            "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
            "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd",
@@ -78,6 +79,9 @@ def load() -> C.CDLL:
     lib.roast_m_shadow_bytes.argtypes = [i64]
     lib.roast_m_shadow_bytes.restype = C.c_size_t
     lib.roast_m_shadow_bf16.argtypes = [vp, i64, vp, vp]
+    lib.roast_m_planes_bytes.argtypes = [i64]
+    lib.roast_m_planes_bytes.restype = C.c_size_t
+    lib.roast_m_planes_bf16.argtypes = [vp, i64, vp, vp]
     lib.roast_mm_fwd.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     lib.roast_mm_bwd_dx.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp]
     for name in ("roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace"):
@@ -103,7 +107,7 @@ def load() -> C.CDLL:
         f = getattr(lib, name)
         if name not in ("roast_status_string", "roast_m_shadow_bytes", "roast_mm_bwd_dM_workspace",
                         "roast_embed_bwd_workspace", "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace",
-                        "roast_embed_bag_bwd_workspace", "roast_mm_bwd_dM_workspace_f32"):
+                        "roast_embed_bag_bwd_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_m_planes_bytes"):
             f.restype = i32
     _lib = lib
     return lib
@@ -214,12 +218,33 @@ def roast_m_shadow_bf16(M, shadow=None, stream=None):
     return shadow
 
 
-def _shadow_ptr(M, M_bf16) -> int:
+def roast_m_planes_bytes(m_size: int) -> int:
+    return int(load().roast_m_planes_bytes(int(m_size)))
+
+
+def roast_m_planes_bf16(M, planes=None, stream=None):
+    """Three bfloat16 planes of M for fp32 roast_mm_fwd / roast_mm_bwd_dx calls with a workspace
+    (pass as M_bf16; make once per update of M)."""
+    torch = _torch()
+    n = roast_m_planes_bytes(M.numel()) // 2
+    if planes is None:
+        planes = torch.empty(n, dtype=torch.bfloat16, device=M.device)
+    if planes.numel() != n:
+        raise ValueError("planes must have roast_m_planes_bytes(|M|) / 2 elements")
+    _check(load().roast_m_planes_bf16(_vec(M, torch.float32, "M"), M.numel(), _vec(planes, torch.bfloat16, "planes"),
+                                      _stream(stream)), "roast_m_planes_bf16")
+    return planes
+
+
+def _shadow_ptr(M, M_bf16, f32: bool = False) -> int:
+    """bf16 calls: the shadow made by roast_m_shadow_bf16; fp32 calls: the planes made by roast_m_planes_bf16."""
     if M_bf16 is None:
         return 0
     torch = _torch()
-    if M_bf16.numel() != roast_m_shadow_bytes(M.numel()) // 2:
-        raise ValueError("M_bf16 must be the tensor made by roast_m_shadow_bf16 for this M")
+    want = (roast_m_planes_bytes(M.numel()) if f32 else roast_m_shadow_bytes(M.numel())) // 2
+    if M_bf16.numel() != want:
+        raise ValueError("M_bf16 must be the tensor made by roast_m_shadow_bf16 (bf16 calls) or "
+                         "roast_m_planes_bf16 (fp32 calls) for this M")
     return _vec(M_bf16, torch.bfloat16, "M_bf16")
 
 
@@ -255,10 +280,11 @@ def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None, ws=N
     yp, ldy = _mat(Y, "Y")
     if ws is not None:
         _check(load().roast_mm_fwd_ws(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"),
-                                      _shadow_ptr(M, M_bf16), yp, ldy, *_ws(ws), _stream(stream)), "roast_mm_fwd_ws")
+                                      _shadow_ptr(M, M_bf16, X.dtype == torch.float32), yp, ldy, *_ws(ws), _stream(stream)), "roast_mm_fwd_ws")
         return Y
     _check(load().roast_mm_fwd(C.byref(desc), _dtype_code(X), I, xp, ldx, _vec(M, torch.float32, "M"),
-                               _shadow_ptr(M, M_bf16), yp, ldy, _stream(stream)), "roast_mm_fwd")
+                               _shadow_ptr(M, M_bf16, X.dtype == torch.float32), yp, ldy, _stream(stream)),
+           "roast_mm_fwd")
     return Y
 
 
@@ -275,11 +301,12 @@ def roast_mm_bwd_dx(desc: RoastMMDesc, dY, M, dX=None, stream=None, M_bf16=None,
     xp, ldx = _mat(dX, "dX")
     if ws is not None:
         _check(load().roast_mm_bwd_dx_ws(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"),
-                                         _shadow_ptr(M, M_bf16), xp, ldx, *_ws(ws), _stream(stream)),
+                                         _shadow_ptr(M, M_bf16, dY.dtype == torch.float32), xp, ldx, *_ws(ws), _stream(stream)),
                "roast_mm_bwd_dx_ws")
         return dX
     _check(load().roast_mm_bwd_dx(C.byref(desc), _dtype_code(dY), I, gp, ldy, _vec(M, torch.float32, "M"),
-                                  _shadow_ptr(M, M_bf16), xp, ldx, _stream(stream)), "roast_mm_bwd_dx")
+                                  _shadow_ptr(M, M_bf16, dY.dtype == torch.float32), xp, ldx, _stream(stream)),
+           "roast_mm_bwd_dx")
     return dX
 
 

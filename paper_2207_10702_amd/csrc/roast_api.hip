@@ -104,6 +104,15 @@ size_t roast_m_shadow_bytes(int64_t m_size) {
   return m_size > 0 ? (size_t)(2 * shadow_stride(m_size)) * 2 : 0;
 }
 
+size_t roast_m_planes_bytes(int64_t m_size) { return m_size > 0 ? m_planes_bytes(m_size) : 0; }
+
+roast_status roast_m_planes_bf16(const float* M, int64_t m_size, void* planes, void* stream) {
+  if (m_size < 0) return ROAST_ERR_ARG;
+  if (m_size == 0) return ROAST_OK;
+  if (!M || !planes || ((uintptr_t)planes & 15) != 0) return ROAST_ERR_ARG;
+  return m_planes_launch(M, m_size, planes, (hipStream_t)stream);
+}
+
 roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream) {
   if (m_size < 0) return ROAST_ERR_ARG;
   if (m_size == 0) return ROAST_OK;
@@ -145,7 +154,7 @@ roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
     const size_t need = roast_mm_fwd_workspace(d, dt, I);
     if (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0) return ROAST_ERR_WORKSPACE;
     if (need) {
-      st = x3_mm_fwd(a, (const float*)X, ldx, M, (float*)Y, ldy, workspace, (hipStream_t)stream);
+      st = x3_mm_fwd(a, (const float*)X, ldx, M, M_bf16, (float*)Y, ldy, workspace, (hipStream_t)stream);
       if (st != ROAST_ERR_UNSUPPORTED) return st;
     }
   }
@@ -175,7 +184,7 @@ roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t 
     const size_t need = roast_mm_bwd_dx_workspace(d, dt, I);
     if (workspace_bytes < need || ((uintptr_t)workspace & 15) != 0) return ROAST_ERR_WORKSPACE;
     if (need) {
-      st = x3_mm_bwd_dx(a, (const float*)dY, ldy, M, (float*)dX, ldx, workspace, (hipStream_t)stream);
+      st = x3_mm_bwd_dx(a, (const float*)dY, ldy, M, M_bf16, (float*)dX, ldx, workspace, (hipStream_t)stream);
       if (st != ROAST_ERR_UNSUPPORTED) return st;
     }
   }

@@ -118,10 +118,13 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
 size_t x3_fwd_workspace(const MMArgs& a);
 size_t x3_dx_workspace(const MMArgs& a);
 size_t x3_dm_workspace(const MMArgs& a);
-roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, float* Y, int64_t ldy, void* ws,
-                       hipStream_t s);
-roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, float* dX, int64_t ldx,
-                          void* ws, hipStream_t s);
+// M_planes (optional): the three plane shadows of M made by m_planes_launch; NULL = made per call in ws
+size_t m_planes_bytes(int64_t m_size);
+roast_status m_planes_launch(const float* M, int64_t m_size, void* planes, hipStream_t s);
+roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, const void* M_planes, float* Y,
+                       int64_t ldy, void* ws, hipStream_t s);
+roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, const void* M_planes,
+                          float* dX, int64_t ldx, void* ws, hipStream_t s);
 roast_status x3_mm_bwd_dM(const MMArgs& a, const float* X, int64_t ldx, const float* dY, int64_t ldy, float* dM,
                           void* ws, hipStream_t s);
 // Gws == nullptr: atomically add lambda*sign*G into dM.  Gws != nullptr: store raw per-split G there

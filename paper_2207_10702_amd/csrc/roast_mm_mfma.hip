@@ -969,8 +969,14 @@ size_t x3_dm_workspace(const MMArgs& a) {
   return x3_dm_ok(a) ? planes_bytes(a.I, a.H) + planes_bytes(a.I, a.O) : 0;
 }
 
-roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, float* Y, int64_t ldy, void* ws,
-                       hipStream_t s) {
+size_t m_planes_bytes(int64_t m_size) { return shadow3_bytes(m_size); }
+
+roast_status m_planes_launch(const float* M, int64_t m_size, void* planes, hipStream_t s) {
+  return shadow3(M, m_size, (uint16_t*)planes, s);
+}
+
+roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float* M, const void* M_planes, float* Y,
+                       int64_t ldy, void* ws, hipStream_t s) {
   if (!x3_fwd_ok(a) || ldy % 4 != 0 || !aligned16(Y) || !aligned16(ws)) return ROAST_ERR_UNSUPPORTED;
   char* base = (char*)ws;
   uint16_t* Xp = (uint16_t*)base;
@@ -978,7 +984,8 @@ roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float
   float* parts = (float*)(base + planes_bytes(a.I, a.H) + shadow3_bytes(a.m_size));
   roast_status st = split_rows(X, a.I, a.H, ldx, Xp, s);
   if (st != ROAST_OK) return st;
-  st = shadow3(M, a.m_size, Mp, s);
+  if (M_planes) Mp = (uint16_t*)M_planes;      // made once per update of M by the caller
+  else st = shadow3(M, a.m_size, Mp, s);
   if (st != ROAST_OK) return st;
   KernArgs p{};
   p.a = a; p.A = Xp; p.lda = pad8(a.H); p.a_plane = a.I * pad8(a.H); p.M = M; p.Mb = Mp;
@@ -989,8 +996,8 @@ roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
-roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, float* dX, int64_t ldx,
-                          void* ws, hipStream_t s) {
+roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const float* M, const void* M_planes,
+                          float* dX, int64_t ldx, void* ws, hipStream_t s) {
   if (!x3_dx_ok(a) || ldx % 4 != 0 || !aligned16(dX) || !aligned16(ws)) return ROAST_ERR_UNSUPPORTED;
   char* base = (char*)ws;
   uint16_t* Gp = (uint16_t*)base;
@@ -998,7 +1005,8 @@ roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const f
   float* parts = (float*)(base + planes_bytes(a.I, a.O) + shadow3_bytes(a.m_size));
   roast_status st = split_rows(dY, a.I, a.O, ldy, Gp, s);
   if (st != ROAST_OK) return st;
-  st = shadow3(M, a.m_size, Mp, s);
+  if (M_planes) Mp = (uint16_t*)M_planes;
+  else st = shadow3(M, a.m_size, Mp, s);
   if (st != ROAST_OK) return st;
   KernArgs p{};
   p.a = a; p.A = Gp; p.lda = pad8(a.O); p.a_plane = a.I * pad8(a.O); p.M = M; p.Mb = Mp;

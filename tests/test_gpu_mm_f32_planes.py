@@ -52,13 +52,14 @@ def test_f32_plane_products_match_oracle(roast, shape, pad):
     assert (nx > 0) == (Z2 % 64 == 0) and (nm > 0) == (Z2 % 32 == 0)
     wf, wx, wm = ws_tensor(nf), ws_tensor(nx), ws_tensor(nm)
     outs = []
+    planes = roast.roast_m_planes_bf16(Md)             # made once, or rebuilt per call in the workspace: same bits
     for rep in range(2):
         for w in (wf, wx, wm):
             w.fill_(0xFF)
         Y = torch.full((I, O + pad), 7.0, dtype=torch.float32, device="cuda")[:, :O]
         dX = torch.full((I, H + pad), 7.0, dtype=torch.float32, device="cuda")[:, :H]
-        roast.roast_mm_fwd(d, Xd, Md, Y, ws=wf)
-        roast.roast_mm_bwd_dx(d, dYd, Md, dX, ws=wx)
+        roast.roast_mm_fwd(d, Xd, Md, Y, ws=wf, M_bf16=planes if rep == 0 else None)
+        roast.roast_mm_bwd_dx(d, dYd, Md, dX, ws=wx, M_bf16=planes if rep == 0 else None)
         outs.append((Y, dX))
     dM = torch.zeros(m, dtype=torch.float32, device="cuda")
     roast.roast_mm_bwd_dM(d, Xd, dYd, dM, roast.ROAST_REDUCE_ATOMIC, wm)

@@ -91,12 +91,11 @@ def test_workspace_contract(roast):
     with pytest.raises(roast.RoastError) as e:
         roast.roast_mm_fwd(d, Xd, Md, ws=ws_tensor(need + 16)[4:])   # misaligned
     assert e.value.status == roast.ROAST_ERR_WORKSPACE
-    # fp32 and large-batch calls need none and ignore what they are given
-    assert roast.roast_mm_fwd_workspace(d, torch.float32, I) == 0
+    # large-batch bf16 calls need none and ignore what they are given
     assert roast.roast_mm_fwd_workspace(d, torch.bfloat16, 16384) == 0
     assert roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, 0) == 0
-    Xf = Xd.to(torch.float32)
-    Y1 = roast.roast_mm_fwd(d, Xf, Md, ws=ws_tensor(16))
-    Y2 = roast.roast_mm_fwd(d, Xf, Md)
+    Xl = torch.randn((16384, H), device="cuda").to(torch.bfloat16)
+    Y1 = roast.roast_mm_fwd(d, Xl, Md, ws=ws_tensor(16))
+    Y2 = roast.roast_mm_fwd(d, Xl, Md)
     torch.cuda.synchronize()
     assert torch.equal(Y1, Y2)
