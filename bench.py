@@ -41,6 +41,9 @@ def parse():
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--mm-only", action="store_true", help="profiling aid: skip the lookup calls")
     p.add_argument("--embed-only", action="store_true", help="profiling aid: skip the ROAST-MM calls")
+    p.add_argument("--hot-path-only", action="store_true",
+                   help="profiling aid: skip the secondary timings made outside the timed steps (optimizer step, "
+                        "pooled lookup), so that a trace holds the hot path's kernels only")
     p.add_argument("--reduce", choices=["atomic", "deterministic"], default="atomic")
     p.add_argument("--workload", choices=["default", "cfg1_single_f32", "cfg2_bert_ffn_bf16", "cfg3_bert_stack_bf16", "cfg5_large_bf16",
                                            "dim_sweep_b512"],
@@ -386,7 +389,7 @@ def main():
 
     # The weight update of a training step (outside `value`): one fused pass that applies the rule,
     # clears dM and refreshes the bf16 shadow.  Timed on config 2's M and on a 64 Mi-entry M (config 5's).
-    if not args.embed_only:
+    if not args.embed_only and not args.hot_path_only:
         result["optimizer"] = time_optimizer(roast, torch, M, dM, Mb)
 
     flop_layer = {"l1": 2.0 * I * l1.H * l1.O, "l2": 2.0 * I * l2.H * l2.O}
@@ -418,32 +421,33 @@ def main():
                                "roofline": {"kernel": "k_embed (embed_fwd)", "bound": "hbm", "achieved": gbs_f,
                                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
                                             "traffic": MEASURED_TRAFFIC_BYTES.get("embed_fwd")}}
-        # the pooled reading of "gather-sum": one output row per sample = the sum of its 26 lookups
-        nb = N // ecfg.n_tables
-        bag_off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * ecfg.n_tables
-        pout = torch.empty((nb, ecfg.D), dtype=torch.float32, device="cuda")
-        pdOut = dOut[:nb]
-        pws = torch.empty(max(roast.roast_embed_bag_bwd_workspace(ed, N, nb, mode), 1), dtype=torch.uint8, device="cuda")
+        if not args.hot_path_only:
+            # the pooled reading of "gather-sum": one output row per sample = the sum of its 26 lookups
+            nb = N // ecfg.n_tables
+            bag_off = torch.arange(nb + 1, dtype=torch.int64, device="cuda") * ecfg.n_tables
+            pout = torch.empty((nb, ecfg.D), dtype=torch.float32, device="cuda")
+            pdOut = dOut[:nb]
+            pws = torch.empty(max(roast.roast_embed_bag_bwd_workspace(ed, N, nb, mode), 1), dtype=torch.uint8, device="cuda")
 
-        def timed(fn, reps=20):
-            for _ in range(3):
-                fn()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                fn()
-            e1.record()
-            torch.cuda.synchronize()
-            return e0.elapsed_time(e1) / reps
+            def timed(fn, reps=20):
+                for _ in range(3):
+                    fn()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
 
-        pf = timed(lambda: roast.roast_embed_bag_fwd(ed, rows, tables, bag_off, eM, pout))
-        pb = timed(lambda: roast.roast_embed_bag_bwd(ed, rows, tables, bag_off, pdOut, edM, mode, pws))
-        edM.zero_()
-        result["embedding"]["pooled_sum_of_26"] = {
-            "bags": nb, "fwd_ms": pf, "bwd_ms": pb, "lookups_per_s_fwd": N / (pf * 1e-3),
-            "lookups_per_s_bwd": N / (pb * 1e-3),
-            # what the gathers deliver: every lookup reads D floats of M (cache-resident) / of dOut
-            "gathered_GBs_fwd": N * ecfg.D * 4 / (pf * 1e-3) / 1e9, "gathered_GBs_bwd": N * ecfg.D * 4 / (pb * 1e-3) / 1e9}
+            pf = timed(lambda: roast.roast_embed_bag_fwd(ed, rows, tables, bag_off, eM, pout))
+            pb = timed(lambda: roast.roast_embed_bag_bwd(ed, rows, tables, bag_off, pdOut, edM, mode, pws))
+            edM.zero_()
+            result["embedding"]["pooled_sum_of_26"] = {
+                "bags": nb, "fwd_ms": pf, "bwd_ms": pb, "lookups_per_s_fwd": N / (pf * 1e-3),
+                "lookups_per_s_bwd": N / (pb * 1e-3),
+                # what the gathers deliver: every lookup reads D floats of M (cache-resident) / of dOut
+                "gathered_GBs_fwd": N * ecfg.D * 4 / (pf * 1e-3) / 1e9, "gathered_GBs_bwd": N * ecfg.D * 4 / (pb * 1e-3) / 1e9}
         if args.embed_only:
             result["value"] = tot
             result["unit"] = "GB/s"
