@@ -1,0 +1,55 @@
+"""Compositions the paper builds from the same operations (Section 3.1: a module is recovered from M
+with L or MM; Section 3.4: global vs local memory sharing), expressed through the existing entry
+points and checked against the oracle:
+  * a bias vector of length O is a one-row lookup (D = O) keyed by the module id;
+  * local memory sharing is one M (and one dM) per module instead of one for all."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2207_10702_amd import workloads as wl
+from tests.util import F32_TOL, rel_err, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def test_bias_vector_is_a_one_row_lookup(roast):
+    rng = np.random.default_rng(41)
+    O, Z, m, module_id = 3072, 64, 47185, 7
+    M = wl.draw_m(rng, m, ("normal", 0.02))
+    h = wl.draw_hash(rng)
+    lam = np.float32(0.5)
+    d = roast.embed_desc(O, Z, m, lam, h)
+    row = to_dev(np.zeros(1, dtype=np.int64))
+    tab = to_dev(np.array([module_id], dtype=np.uint32))
+    b = roast.roast_embed_fwd(d, row, tab, to_dev(M))
+    ref = oracle.embed_fwd(h, O, Z, float(lam), np.zeros(1, dtype=np.int64), np.array([module_id], dtype=np.uint32), M)
+    assert rel_err(to_host_f64(b), ref) <= 1e-7
+    # its gradient: the column sums of dY (what a bias receives) scattered back into dM
+    dY = rng.standard_normal((500, O)).astype(np.float32)
+    db = torch.from_numpy(dY).cuda().sum(dim=0, keepdim=True)
+    dM = torch.zeros(m, dtype=torch.float32, device="cuda")
+    roast.roast_embed_bwd(d, row, tab, db, dM)
+    ref_dM = oracle.embed_bwd(h, O, Z, m, float(lam), np.zeros(1, dtype=np.int64), np.array([module_id], dtype=np.uint32),
+                              to_host_f64(db))
+    assert rel_err(to_host_f64(dM), ref_dM) <= F32_TOL
+
+
+def test_local_memory_sharing_is_one_m_per_module(roast):
+    rng = np.random.default_rng(42)
+    I, H, O, Z = 300, 128, 192, 64
+    h = wl.draw_hash(rng)
+    X = wl.draw_act(rng, I, H, "f32")
+    dY = wl.draw_act(rng, I, O, "f32")
+    for layer, m in ((0, 9000), (1, 5000)):          # two modules, two arrays of different size
+        M = wl.draw_m(rng, m, ("normal", 0.05))
+        d = roast.mm_desc(H, O, Z, Z, m, layer, 1.0, h)
+        Y = roast.roast_mm_fwd(d, to_dev(X), to_dev(M))
+        dM = torch.zeros(m, dtype=torch.float32, device="cuda")
+        roast.roast_mm_bwd_dM(d, to_dev(X), to_dev(dY), dM)
+        W = oracle.materialize_w(h, layer, H, O, Z, Z, 1.0, M)
+        assert rel_err(to_host_f64(Y), oracle.mm_fwd(X.astype(np.float64), W)) <= F32_TOL
+        ref = oracle.mm_bwd_dm(h, layer, Z, Z, m, 1.0, X.astype(np.float64), dY.astype(np.float64))
+        assert rel_err(to_host_f64(dM), ref) <= F32_TOL
