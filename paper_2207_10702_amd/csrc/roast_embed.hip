@@ -9,6 +9,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 #include "roast_internal.hpp"
@@ -610,12 +611,12 @@ roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* 
   hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, (int64_t)p.nb);
   const int rows_wg = kRouteItems / (int)a.C;
   const size_t lds_route = (size_t)kRouteItems * (4 + 2) + (size_t)2 * p.nb * 4 + (a.bag_off ? (size_t)rows_wg * 4 : 0);
-  static bool configured = false;   // per instantiation
-  if (!configured) {
+  static std::atomic<bool> configured{false};   // per instantiation; a race between host threads only repeats the call
+  if (!configured.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048) != hipSuccess)
       return ROAST_ERR_HIP;
-    configured = true;
+    configured.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL(k_embed_route<FIXED>, dim3((unsigned)((a.N + rows_wg - 1) / rows_wg)), dim3(256), lds_route, s, a,
                      p.r_log2, p.nb, p.cap, walk_ok(a), rows, tables, cursor, list, dOut, dM, pbits, fs, acc);

@@ -34,6 +34,8 @@
 // contiguous band of output row blocks.
 #include <type_traits>
 
+#include <atomic>
+
 #include "roast_internal.hpp"
 
 namespace roast {
@@ -711,12 +713,12 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const dim3 grid((unsigned)((total + 7) / 8 * 8));
   constexpr int smem = smem_bytes<MODE, BM, BN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
-  static bool configured = false;   // one attribute call per instantiation per process
-  if (!configured) {
+  static std::atomic<bool> configured{false};   // per instantiation and process; a race between host threads only repeats the call
+  if (!configured.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
-    configured = true;
+    configured.store(true, std::memory_order_release);
   }
   hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>), grid, dim3((WGM * WGN + 8) * 64), smem, s, p);
   return hip_status(hipGetLastError());
