@@ -16,6 +16,10 @@
  *                               function"; the family used here is the
  *                               Carter-Wegman multiply-add-mod-prime family,
  *                               ((c0*k0 + c1*k1 + c2*k2 + c3) mod P) mod range.
+ *   - oracle_elem_sign        : the per-element reading of the sign map g
+ *                               (use_sign == 2; the theory of Section 3.4
+ *                               writes g(i) per parameter), same hash family,
+ *                               keyed by the element's coordinates.
  *   - oracle_element_index    : the ROAST-MM mapping equation of Section 3.1,
  *                               W[i,j] = lambda * M[h2(C1,C2) + Z2*O1 + O2].
  *   - oracle_materialize_w    : that equation, evaluated element by element.
@@ -49,7 +53,8 @@ typedef struct {
   uint64_t P;              /* prime modulus, 2 <= P < 2^32                      */
   uint64_t a0, a1, a2, a3; /* offset hash coefficients, all < P                 */
   uint64_t s0, s1, s2, s3; /* sign hash coefficients, all < P                   */
-  uint32_t use_sign;       /* 0: sign is +1 everywhere                          */
+  uint32_t use_sign;       /* 0: sign is +1 everywhere; 1: one sign per block    */
+                           /* (tile / chunk); 2: one sign per element            */
   uint32_t align;          /* offsets are multiples of align (1 = the paper)    */
 } oracle_hash_t;
 
@@ -73,13 +78,22 @@ int oracle_locate(const oracle_hash_t* h, uint64_t k0, uint64_t k1, uint64_t k2,
   uint64_t nslots = (uint64_t)(m_size - len) / h->align + 1;
   uint64_t u = cw_value(h->P, h->a0, h->a1, h->a2, h->a3, k0, k1, k2);
   *off = (int64_t)(h->align * (u % nslots));
-  if (h->use_sign) {
+  if (h->use_sign == 1) {
     uint64_t v = cw_value(h->P, h->s0, h->s1, h->s2, h->s3, k0, k1, k2);
     *sgn = 1 - 2 * (int32_t)(v & 1u);
   } else {
-    *sgn = 1;
+    *sgn = 1;   /* no sign, or the sign belongs to the element (oracle_elem_sign) */
   }
   return 0;
+}
+
+/* Per-element variant of the sign map g (use_sign == 2): the same sign hash, keyed by the
+ * element's own coordinates -- (layer, i, j) for W[i,j], (table, row, i) for element i of a looked
+ * up row -- instead of the block's.  +1 in the other modes. */
+int32_t oracle_elem_sign(const oracle_hash_t* h, uint64_t k0, uint64_t k1, uint64_t k2) {
+  if (h->use_sign != 2) return 1;
+  uint64_t v = cw_value(h->P, h->s0, h->s1, h->s2, h->s3, k0, k1, k2);
+  return 1 - 2 * (int32_t)(v & 1u);
 }
 
 /* Tile grid of one ROAST-MM layer: ceil(H/Z1) x ceil(O/Z2) tiles, row-major in
@@ -106,6 +120,7 @@ int oracle_element_index(const oracle_hash_t* h, uint32_t layer, int32_t Z1, int
   int64_t base;
   if (oracle_locate(h, layer, (uint64_t)c1, (uint64_t)c2, m_size, (int64_t)Z1 * Z2, &base, sgn)) return 1;
   *idx = base + (int64_t)Z2 * o1 + o2;
+  *sgn *= oracle_elem_sign(h, layer, (uint64_t)i, (uint64_t)j);
   return 0;
 }
 
@@ -227,8 +242,10 @@ int oracle_embed_fwd(const oracle_hash_t* h, int64_t D, int32_t Z, int64_t m_siz
     for (int64_t c = 0; c * Z < D; ++c) {
       int64_t base; int32_t s;
       if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)c, m_size, Z, &base, &s)) return 1;
-      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i)
-        out[n * D + i] = lambda * (double)s * (double)M[base + i % Z];
+      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i) {
+        int32_t g = s * oracle_elem_sign(h, tables[n], (uint64_t)rows[n], (uint64_t)i);
+        out[n * D + i] = lambda * (double)g * (double)M[base + i % Z];
+      }
     }
   }
   return 0;
@@ -243,8 +260,10 @@ int oracle_embed_bwd(const oracle_hash_t* h, int64_t D, int32_t Z, int64_t m_siz
     for (int64_t c = 0; c * Z < D; ++c) {
       int64_t base; int32_t s;
       if (oracle_locate(h, tables[n], (uint64_t)rows[n], (uint64_t)c, m_size, Z, &base, &s)) return 1;
-      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i)
-        dM[base + i % Z] += lambda * (double)s * dOut[n * D + i];
+      for (int64_t i = c * Z; i < D && i < (c + 1) * Z; ++i) {
+        int32_t g = s * oracle_elem_sign(h, tables[n], (uint64_t)rows[n], (uint64_t)i);
+        dM[base + i % Z] += lambda * (double)g * dOut[n * D + i];
+      }
     }
   }
   return 0;

@@ -32,9 +32,8 @@
 // forward / dX goes through LDS (the operand stages, free by then) so that global stores are 16
 // bytes per lane and row-contiguous.  Workgroups are numbered so that each XCD's L2 serves a
 // contiguous band of output row blocks.
-#include <type_traits>
-
 #include <atomic>
+#include <type_traits>
 
 #include "roast_internal.hpp"
 

@@ -21,7 +21,8 @@ MUTANTS = {
     "dx_uses_untransposed_w": ("for (int64_t o = 0; o < O; ++o) acc += g[o] * w[o];", "for (int64_t o = 0; o < O; ++o) acc += g[o] * W[(o % H) * O + (k % O)];"),
     "dw_contracts_wrong_index": ("double x = X[i * H + k];\n      const double* g = dY + i * O;", "double x = X[i * H + (H - 1 - k)];\n      const double* g = dY + i * O;"),
     "lookup_uses_chunk_number_as_offset": ("(double)M[base + i % Z];", "(double)M[base + (i / Z) % Z];"),
-    "lookup_gradient_missing_sign": ("dM[base + i % Z] += lambda * (double)s * dOut[n * D + i];", "dM[base + i % Z] += lambda * dOut[n * D + i];"),
+    "lookup_gradient_missing_sign": ("dM[base + i % Z] += lambda * (double)g * dOut[n * D + i];", "dM[base + i % Z] += lambda * dOut[n * D + i];"),
+    "element_sign_keyed_by_the_block": ("*sgn *= oracle_elem_sign(h, layer, (uint64_t)i, (uint64_t)j);", "*sgn *= oracle_elem_sign(h, layer, (uint64_t)c1, (uint64_t)c2);"),
     "bf16_ties_round_up": ("(rest == 0x8000u && (keep & 1u))", "(rest == 0x8000u)"),
     "offset_hash_ignores_second_key": ("uint64_t t1 = (c1 * (k1 % P)) % P;", "uint64_t t1 = 0; (void)c1; (void)k1;"),
     "product_not_reduced_before_sum": ("uint64_t t2 = (c2 * (k2 % P)) % P;", "uint64_t t2 = (c2 * k2);"),
@@ -40,7 +41,8 @@ def test_pins_catch_planted_mistake(name, tmp_path):
                    check=True)
     env = dict(os.environ, ROAST_ORACLE_LIB=str(lib))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        os.path.join(ROOT, "tests", "test_sign_variant_pins.py")],
                        cwd=ROOT, env=env, capture_output=True, text=True)
     assert r.returncode == 1, f"mutant {name} survived the pins:\n{r.stdout[-2000:]}"
     assert "failed" in r.stdout

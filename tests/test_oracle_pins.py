@@ -24,7 +24,7 @@ def big_locate(h, k0, k1, k2, m_size, length):
     u = (h["a0"] * k0 + h["a1"] * k1 + h["a2"] * k2 + h["a3"]) % P
     nslots = (m_size - length) // h["align"] + 1
     off = h["align"] * (u % nslots)
-    if h["use_sign"]:
+    if h["use_sign"] == 1:
         v = (h["s0"] * k0 + h["s1"] * k1 + h["s2"] * k2 + h["s3"]) % P
         return off, 1 - 2 * (v & 1)
     return off, 1
