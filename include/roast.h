@@ -62,7 +62,14 @@ typedef enum { ROAST_REDUCE_ATOMIC = 0, ROAST_REDUCE_DETERMINISTIC = 1 } roast_r
  *     u      = ((a0*(k0 mod P)) mod P + (a1*(k1 mod P)) mod P + (a2*(k2 mod P)) mod P + a3) mod P
  *     offset = align * (u mod (floor((|M| - block) / align) + 1))
  *     v      = the same form with s0..s3
- *     sign   = use_sign ? 1 - 2*(v & 1) : +1
+ *     sign   = 1 - 2*(v & 1)
+ *
+ * use_sign = 0: no sign (+1 everywhere).  use_sign = 1: one sign per block (tile or chunk), v keyed
+ * like the offset -- the reading this library takes as the default, and the one its fast kernels
+ * implement.  use_sign = 2: one sign per element, v keyed by the element's own coordinates
+ * ((layer_id, i, j) for W[i,j]; (table_id, row, d) for element d of a looked-up row), the form the
+ * analysis of Section 3.4 uses; this variant runs on the generic kernels.  Other values:
+ * ROAST_ERR_RANGE.
  *
  * ROAST-MM keys: (layer_id, x, y) with x the tile row (along H) and y the tile column (along O),
  * block = Z1*Z2.  Lookup keys: (table_id, row, chunk), block = Z.  "Each module uses independent

@@ -8,7 +8,7 @@ using namespace roast;
 namespace {
 
 roast_status check_hash(const roast_hash& h) {
-  if (h.P < 2 || h.P >= (1ull << 32) || h.align < 1) return ROAST_ERR_RANGE;
+  if (h.P < 2 || h.P >= (1ull << 32) || h.align < 1 || h.use_sign > 2) return ROAST_ERR_RANGE;
   const uint64_t c[8] = {h.a0, h.a1, h.a2, h.a3, h.s0, h.s1, h.s2, h.s3};
   for (uint64_t v : c)
     if (v >= h.P) return ROAST_ERR_RANGE;

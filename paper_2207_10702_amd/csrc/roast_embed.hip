@@ -160,7 +160,8 @@ __global__ __launch_bounds__(256) void k_embed_elem(EmbedArgs a, const int64_t* 
   if (e >= a.N * a.D) return;
   const int64_t n = e / a.D, i = e - n * a.D, c = i / a.Z, o = i - c * a.Z;
   const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
-  const float scale = a.lambda * (float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
+  const float scale = a.lambda * (float)(block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c) *
+                                         elem_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)i));
   if (!BWD) out[e] = scale * M[off + o];
   else unsafeAtomicAdd(dM + off + o, scale * dOut[grad_row(a, n) * a.D + i]);
 }
@@ -269,7 +270,8 @@ __global__ __launch_bounds__(256) void k_embed_bag_fwd_elem(EmbedArgs a, const i
   double acc = 0.0;
   for (int64_t n = n0; n < n1; ++n) {
     const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
-    acc += (double)((float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c) * M[off + o]);
+    acc += (double)((float)(block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c) *
+                            elem_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)i)) * M[off + o]);
   }
   out[e] = (float)((double)a.lambda * acc);
 }
@@ -279,7 +281,8 @@ inline int walk_ok(const EmbedArgs& a) { return (uint64_t)a.C <= a.hash.P.d ? 1 
 template <bool BWD>
 roast_status launch_embed(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
                           float* out, const float* dOut, float* dM, hipStream_t s) {
-  if (a.m_size >= (1ll << 31) || a.C > kMaxC) {
+  // (the chunk kernels carry one sign per chunk: per-element signs take the per-element kernel)
+  if (a.m_size >= (1ll << 31) || a.C > kMaxC || a.hash.use_sign == 2) {
     const int64_t blocks = (a.N * a.D + 255) / 256;
     if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((k_embed_elem<BWD>), dim3((unsigned)blocks), dim3(256), 0, s, a, rows, tables, M, out, dOut, dM);
@@ -333,7 +336,8 @@ inline BucketPlan bucket_plan(const EmbedArgs& a) {
   BucketPlan p{};
   p.n_items = a.N * a.C;
   p.ok = (a.Z % 4 == 0) && (a.D % a.Z == 0) && a.m_size < (1ll << 31) && p.n_items < (1ll << 31) && a.Z <= 1024 &&
-         a.C <= kMaxC && a.B * a.C < (1ll << 31);   // (B = 0 unless pooled)
+         a.C <= kMaxC && a.B * a.C < (1ll << 31) &&  // (B = 0 unless pooled)
+         a.hash.use_sign != 2;                       // list entries carry one sign per chunk
   if (!p.ok) return p;
   int r = 12;
   while ((1 << r) < kMaxR && ((a.m_size + (1ll << r) - 1) >> r) > kMaxBuckets) ++r;
@@ -408,7 +412,8 @@ __global__ __launch_bounds__(256) void k_embed_fixed_elem(EmbedArgs a, int pbits
   const double scale = fixed_scale(fs, a.lambda, pbits);
   const int64_t n = e / a.D, i = e - n * a.D, c = i / a.Z, o = i - c * a.Z;
   const int64_t off = block_offset(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
-  const float sc = a.lambda * (float)block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c);
+  const float sc = a.lambda * (float)(block_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)c) *
+                                      elem_sign(a.hash, tables[n], (uint64_t)rows[n], (uint64_t)i));
   atomicAdd(acc + off + o, to_fixed(sc * dOut[grad_row(a, n) * a.D + i], scale));
 }
 
@@ -700,7 +705,7 @@ roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const ui
 
 roast_status embed_bag_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
                                   float* out, hipStream_t s) {
-  if (a.m_size >= (1ll << 31) || a.C > kMaxC) {
+  if (a.m_size >= (1ll << 31) || a.C > kMaxC || a.hash.use_sign == 2) {
     const int64_t blocks = (a.B * a.D + 255) / 256;
     if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(k_embed_bag_fwd_elem, dim3((unsigned)blocks), dim3(256), 0, s, a, rows, tables, M, out);

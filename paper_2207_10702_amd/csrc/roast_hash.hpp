@@ -79,9 +79,15 @@ __host__ __device__ inline int64_t block_offset(const HashDev& h, uint64_t k0, u
   return (int64_t)((uint64_t)h.align * bmod(u, h.slots));
 }
 
-// +1 or -1
+// +1 or -1: the sign of a block (use_sign == 1) ...
 __host__ __device__ inline int block_sign(const HashDev& h, uint64_t k0, uint64_t k1, uint64_t k2) {
-  if (!h.use_sign) return 1;
+  if (h.use_sign != 1) return 1;
+  uint64_t v = cw(h.P, h.s0, h.s1, h.s2, h.s3, k0, k1, k2);
+  return 1 - 2 * (int)(v & 1ull);
+}
+// ... or of a single element, keyed by the element's own coordinates (use_sign == 2)
+__host__ __device__ inline int elem_sign(const HashDev& h, uint64_t k0, uint64_t k1, uint64_t k2) {
+  if (h.use_sign != 2) return 1;
   uint64_t v = cw(h.P, h.s0, h.s1, h.s2, h.s3, k0, k1, k2);
   return 1 - 2 * (int)(v & 1ull);
 }
@@ -128,7 +134,7 @@ struct ChunkWalk {
     *off = (int64_t)((uint64_t)h.align * mod_slots32(h, (uint32_t)u));
     uint64_t v = (uint64_t)r.v + ts;
     if (v >= P) v -= P;
-    *sgn = h.use_sign ? 1 - 2 * (int)(v & 1ull) : 1;
+    *sgn = h.use_sign == 1 ? 1 - 2 * (int)(v & 1ull) : 1;
   }
   __host__ __device__ inline void next(const HashDev& h) {
     const uint32_t P = (uint32_t)h.P.d;

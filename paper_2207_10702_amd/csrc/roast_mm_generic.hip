@@ -44,6 +44,7 @@ __device__ inline float w_elem(const MMArgs& a, const float* __restrict__ M, Til
   tile_of(a, tc, x, y);
   const int64_t pos = (int64_t)a.Z2 * (h - x * a.Z1) + (o - y * a.Z2);
   float v = tc.sgn * M[tc.off + pos];
+  if (a.hash.use_sign == 2) v *= (float)elem_sign(a.hash, a.layer, (uint64_t)h, (uint64_t)o);
   if (kBf16) v = bf16_bits_to_float(float_to_bf16_bits(v));
   return v;
 }
@@ -168,7 +169,8 @@ __global__ __launch_bounds__(256) void k_generic_dm(MMArgs a, const T* __restric
         const int x = gh / a.Z1, y = go / a.Z2;
         tile_of(a, tc, x, y);
         const int64_t pos = (int64_t)a.Z2 * (gh - x * a.Z1) + (go - y * a.Z2);
-        unsafeAtomicAdd(dM + tc.off + pos, a.lambda * tc.sgn * acc[r][c]);
+        const float es = a.hash.use_sign == 2 ? (float)elem_sign(a.hash, a.layer, (uint64_t)gh, (uint64_t)go) : 1.f;
+        unsafeAtomicAdd(dM + tc.off + pos, a.lambda * tc.sgn * es * acc[r][c]);
       }
     }
   }

@@ -876,12 +876,13 @@ roast_status shadow3(const float* M, int64_t m_size, uint16_t* out, hipStream_t 
   return hip_status(hipGetLastError());
 }
 
+// (the tile table holds one sign per tile: per-element signs, use_sign == 2, go to the generic kernels)
 bool mfma_fwd_ok(const MMArgs& a) {
-  return a.Z1 % BK == 0 && a.H % a.Z1 == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
+  return a.hash.use_sign != 2 && a.Z1 % BK == 0 && a.H % a.Z1 == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
          a.nTx * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
 }
 bool mfma_dx_ok(const MMArgs& a) {
-  return a.Z2 % BK == 0 && a.O % a.Z2 == 0 && a.H % 8 == 0 && a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
+  return a.hash.use_sign != 2 && a.Z2 % BK == 0 && a.O % a.Z2 == 0 && a.H % 8 == 0 && a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
 }
 
 }  // namespace
@@ -930,6 +931,8 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   if (a.Z1 % 32 != 0 || a.Z2 % 32 != 0 || a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
       !aligned16(X) || !aligned16(dY) || a.H < BM / 32 || a.O < BN / 32)
     return ROAST_ERR_UNSUPPORTED;
+  // the atomic epilogue applies one sign per tile; raw products for the deterministic reduction are sign-free
+  if (Gws == nullptr && a.hash.use_sign == 2) return ROAST_ERR_UNSUPPORTED;
   if ((cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   const int64_t tiles = cdiv(a.H, BM) * cdiv(a.O, BN);
   if (Gws == nullptr) splits = dm_pick_splits(tiles, a.I);
@@ -950,7 +953,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
 bool x3_fwd_ok(const MMArgs& a) { return mfma_fwd_ok(a) && a.Z2 % 8 == 0 && a.O % 4 == 0; }
 bool x3_dx_ok(const MMArgs& a) { return mfma_dx_ok(a) && a.H % 4 == 0; }
 bool x3_dm_ok(const MMArgs& a) {
-  return a.Z1 % 32 == 0 && a.Z2 % 32 == 0 && a.H % 8 == 0 && a.O % 8 == 0 && a.H >= kBM / 32 && a.O >= kBN / 32 &&
+  return a.hash.use_sign != 2 && a.Z1 % 32 == 0 && a.Z2 % 32 == 0 && a.H % 8 == 0 && a.O % 8 == 0 && a.H >= kBM / 32 && a.O >= kBN / 32 &&
          (cdiv(kBM, a.Z1) + 1) * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
 }
 int x3_fwd_splits(const MMArgs& a) { return mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), 6 * a.H); }

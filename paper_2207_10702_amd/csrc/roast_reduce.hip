@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void k_dm_gather(MMArgs a, int splits, const f
     if (h >= a.H || c >= a.O) continue;
     float acc = 0.f;
     for (int s = 0; s < splits; ++s) acc += G[((int64_t)s * a.H + h) * a.O + c];
-    total += a.lambda * (float)sgn[t] * acc;
+    const float es = a.hash.use_sign == 2 ? (float)elem_sign(a.hash, a.layer, (uint64_t)h, (uint64_t)c) : 1.f;
+    total += a.lambda * (float)sgn[t] * es * acc;
     any = true;
   }
   if (any) dM[j] += total;
@@ -134,6 +135,7 @@ __global__ __launch_bounds__(256) void k_dm_scatter(MMArgs a, int splits, int ro
 // ---- split products through the workspace, then one scatter (the fast path of the ATOMIC mode when
 // the caller provides a workspace): S*H*O floats.
 int dm_ws_splits(const MMArgs& a) {
+  if (a.hash.use_sign == 2) return 0;   // the scatter pass applies one sign per tile
   const int s = dm_pick_splits(((a.H + 255) / 256) * ((a.O + 127) / 128), a.I);
   return s > 1 ? s : 0;               // a single split gains nothing over direct atomics
 }
