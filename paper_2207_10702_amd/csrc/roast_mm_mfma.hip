@@ -773,19 +773,34 @@ __device__ inline void split3(float x, uint16_t* hi, uint16_t* mid, uint16_t* lo
   *lo = (uint16_t)(__builtin_bit_cast(uint32_t, r2) >> 16);
 }
 
-// planes[s][r * ldo + c] = plane s of src[r * ld + c]
+// planes[s][r * ldo + c] = plane s of src[r * ld + c]; VEC consecutive columns per thread
+// (VEC = 4: 16-byte loads, 8-byte stores; needs cols % 4 == 0, ld % 4 == 0 and a 16-byte aligned src)
+template <int VEC>
 __global__ __launch_bounds__(256) void k_split3_rows(const float* __restrict__ src, int64_t rows, int64_t cols,
                                                      int64_t ld, uint16_t* __restrict__ out, int64_t ldo,
                                                      int64_t plane) {
+  const int64_t cpr = cols / VEC;
   const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (t >= rows * cols) return;
-  const int64_t r = t / cols, c = t - r * cols;
-  uint16_t h, m, l;
-  split3(src[r * ld + c], &h, &m, &l);
+  if (t >= rows * cpr) return;
+  const int64_t r = t / cpr, c = (t - r * cpr) * VEC;
+  uint16_t h[VEC], m[VEC], l[VEC];
+  if constexpr (VEC == 4) {
+    const float4v v = __builtin_nontemporal_load(reinterpret_cast<const float4v*>(src + r * ld + c));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) split3(v[i], &h[i], &m[i], &l[i]);
+  } else {
+    split3(src[r * ld + c], &h[0], &m[0], &l[0]);
+  }
   uint16_t* o = out + r * ldo + c;
-  o[0] = h;
-  o[plane] = m;
-  o[2 * plane] = l;
+  if constexpr (VEC == 4) {
+    *reinterpret_cast<uint2v*>(o) = uint2v{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+    *reinterpret_cast<uint2v*>(o + plane) = uint2v{(uint32_t)m[0] | ((uint32_t)m[1] << 16), (uint32_t)m[2] | ((uint32_t)m[3] << 16)};
+    *reinterpret_cast<uint2v*>(o + 2 * plane) = uint2v{(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16)};
+  } else {
+    o[0] = h[0];
+    o[plane] = m[0];
+    o[2 * plane] = l[0];
+  }
 }
 
 // Three shadows of M, one per plane, each in the two-copy layout of k_shadow_bf16:
@@ -863,10 +878,15 @@ size_t planes_bytes(int64_t rows, int64_t cols) { return up256((size_t)3 * rows 
 size_t shadow3_bytes(int64_t m_size) { return up256((size_t)3 * 2 * shadow_stride_of(m_size) * 2); }
 
 roast_status split_rows(const float* src, int64_t rows, int64_t cols, int64_t ld, uint16_t* out, hipStream_t s) {
-  const int64_t blocks = cdiv(rows * cols, 256);
+  const bool vec = cols % 4 == 0 && ld % 4 == 0 && aligned16(src);
+  const int64_t blocks = cdiv(rows * (vec ? cols / 4 : cols), 256);
   if (blocks > 0x7fffffffll) return ROAST_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(k_split3_rows, dim3((unsigned)blocks), dim3(256), 0, s, src, rows, cols, ld, out, pad8(cols),
-                     rows * pad8(cols));
+  if (vec)
+    hipLaunchKernelGGL(k_split3_rows<4>, dim3((unsigned)blocks), dim3(256), 0, s, src, rows, cols, ld, out, pad8(cols),
+                       rows * pad8(cols));
+  else
+    hipLaunchKernelGGL(k_split3_rows<1>, dim3((unsigned)blocks), dim3(256), 0, s, src, rows, cols, ld, out, pad8(cols),
+                       rows * pad8(cols));
   return hip_status(hipGetLastError());
 }
 

@@ -29,7 +29,7 @@ def ws_tensor(nbytes):
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-@pytest.mark.parametrize("pad", [0, 4])
+@pytest.mark.parametrize("pad", [0, 4, 3])      # 3: rows not 16-byte aligned (scalar pre-pass; forward / dX fall back)
 def test_f32_plane_products_match_oracle(roast, shape, pad):
     I, H, O, Z1, Z2, m = shape
     rng = np.random.default_rng(4000 + I + pad)
