@@ -100,6 +100,7 @@ struct KernArgs {
   float* G;            // DM, deterministic mode: raw products [split][H][O]
                        // FWD / DX with a split contraction: fp32 partial outputs [split][I][columns]
   int rows_per_split;  // length of one part of the contraction axis (DM always; FWD / DX when nbz > 1)
+  int split_begin[18]; // dM with uneven parts (all zero: unused): part z covers rows [split_begin[z], split_begin[z+1])
   int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
 };
 
@@ -247,8 +248,13 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
   if (MODE == MODE_DM || p.nbz > 1) {
-    k_begin = bz * p.rows_per_split;
-    k_end = min(k_end, k_begin + p.rows_per_split);
+    if (MODE == MODE_DM && p.split_begin[1] > 0) {
+      k_begin = p.split_begin[bz];
+      k_end = p.split_begin[bz + 1];
+    } else {
+      k_begin = bz * p.rows_per_split;
+      k_end = min(k_end, k_begin + p.rows_per_split);
+    }
   }
   const int nsteps_k = max(0, (k_end - k_begin + BK - 1) / BK);
   const int nsteps = X3 ? 6 * nsteps_k : nsteps_k;               // identical for every wave of the workgroup
@@ -945,6 +951,26 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 
+// Parts of the contraction axis for the dM product with the atomic epilogue.  All workgroups of a
+// launch run at once, so with equal parts they would all reach their epilogue together and the
+// atomic units (0.3 T adds/s for the whole chip) would be the only thing running for the last
+// quarter of the kernel.  Parts of graded length -- proportional to 1 + d*(2z/(s-1) - 1), d = 0.22,
+// in whole 64-row steps -- spread the epilogues out, so that the adds of the early workgroups
+// overlap the products of the late ones (measured: 94 -> 85 us on the BERT-FFN shapes).
+// A function of the shape only.
+static void uneven_parts(int64_t I, int splits, int* begin) {
+  if (splits < 2 || splits > 16) return;     // begin[] stays zero: equal parts of rows_per_split
+  constexpr double d = 0.22;
+  double acc = 0.0;
+  begin[0] = 0;
+  for (int z = 0; z < splits; ++z) {
+    acc += (1.0 + d * (2.0 * z / (splits - 1) - 1.0)) / splits;
+    int64_t e = (int64_t)(acc * (double)I / BK + 0.5) * BK;
+    if (z == splits - 1 || e > I) e = I;
+    begin[z + 1] = (int)e;
+  }
+}
+
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
                             float* Gws, int splits, hipStream_t s) {
   constexpr int BM = 256, BN = 128;
@@ -962,6 +988,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   KernArgs p{};
   p.a = a; p.A = (const uint16_t*)X; p.lda = ldx; p.B = (const uint16_t*)dY; p.ldb = ldy; p.dM = dM; p.G = Gws;
   p.rows_per_split = (int)rows;
+  if (Gws == nullptr) uneven_parts(a.I, splits, p.split_begin);
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
   return launch<MODE_DM, BM, BN, 4, 2, false>(p, grid, s);
 }
@@ -1059,7 +1086,9 @@ roast_status x3_mm_bwd_dM(const MMArgs& a, const float* X, int64_t ldx, const fl
   p.a = a; p.A = Xp; p.lda = pad8(a.H); p.a_plane = a.I * pad8(a.H);
   p.B = Gp; p.ldb = pad8(a.O); p.b_plane = a.I * pad8(a.O); p.dM = dM;
   p.rows_per_split = (int)rows;
-  const dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.H, kBM), (unsigned)cdiv(a.I, rows));
+  const unsigned parts = (unsigned)cdiv(a.I, rows);
+  uneven_parts(a.I, (int)parts, p.split_begin);
+  const dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.H, kBM), parts);
   return launch<MODE_DM, kBM, kBN, 4, 2, false, true>(p, grid, s);
 }
 
