@@ -34,59 +34,78 @@ inline DetLayout det_layout(const MMArgs& a, int splits) {
 }
 
 // rank of tile t among all tiles by (offset, id); writes the sorted offsets and the permutation.
+// Sixteen lanes share a tile: each counts the smaller keys among every sixteenth key of the staged
+// block, and the counts are added up across the lanes (integers: any order).
+constexpr int kRankLanes = 16;
 __global__ __launch_bounds__(256) void k_rank_tiles(int64_t nT, const int64_t* __restrict__ off,
                                                     int64_t* __restrict__ sorted_off, uint32_t* __restrict__ order) {
   __shared__ int64_t buf[256];
-  const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t t = ((int64_t)blockIdx.x * 256 + threadIdx.x) / kRankLanes;
+  const int sub = threadIdx.x % kRankLanes;
   const int64_t mine = t < nT ? off[t] : 0;
-  int64_t rank = 0;
+  int rank = 0;
   for (int64_t base = 0; base < nT; base += 256) {
     const int64_t u = base + threadIdx.x;
     buf[threadIdx.x] = u < nT ? off[u] : INT64_MAX;
     __syncthreads();
     const int lim = (int)min((int64_t)256, nT - base);
-    for (int q = 0; q < lim; ++q) {
+    for (int q = sub; q < lim; q += kRankLanes) {
       const int64_t o = buf[q];
       rank += (o < mine || (o == mine && base + q < t)) ? 1 : 0;
     }
     __syncthreads();
   }
-  if (t < nT) {
+#pragma unroll
+  for (int d = kRankLanes / 2; d >= 1; d >>= 1) rank += __shfl_xor(rank, d, 64);
+  if (t < nT && sub == 0) {
     sorted_off[rank] = mine;
     order[rank] = (uint32_t)t;
   }
 }
 
+// dM[j] += sum over every virtual weight that lands on slot j, in a fixed order: the tiles that cover
+// j in rank order, dealt round-robin to the eight lanes that share the slot, each lane adding its
+// tiles (and their parts) in order, then a butterfly over the eight partial sums -- every level adds
+// the same two values on both lanes, and fp addition is commutative, so all lanes agree bit for bit.
+constexpr int kGatherLanes = 8;
 __global__ __launch_bounds__(256) void k_dm_gather(MMArgs a, int splits, const float* __restrict__ G,
                                                    const int64_t* __restrict__ sorted_off,
                                                    const uint32_t* __restrict__ order, const int8_t* __restrict__ sgn,
                                                    float* __restrict__ dM) {
-  const int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (j >= a.m_size) return;
+  const int64_t j = ((int64_t)blockIdx.x * 256 + threadIdx.x) / kGatherLanes;
+  const int sub = threadIdx.x % kGatherLanes;
+  const bool live = j < a.m_size;
   const int64_t nT = a.nTx * a.nTy, L = (int64_t)a.Z1 * a.Z2;
-  // first ranked tile with offset > j - L
-  int64_t lo = 0, hi = nT;
-  while (lo < hi) {
-    const int64_t mid = (lo + hi) >> 1;
-    if (sorted_off[mid] > j - L) hi = mid; else lo = mid + 1;
-  }
   float total = 0.f;
-  bool any = false;
-  for (int64_t q = lo; q < nT; ++q) {
-    const int64_t o = sorted_off[q];
-    if (o > j) break;
-    const uint32_t t = order[q];
-    const int64_t p = j - o;
-    const int64_t h = (int64_t)(t / a.nTy) * a.Z1 + p / a.Z2;
-    const int64_t c = (int64_t)(t % a.nTy) * a.Z2 + p % a.Z2;
-    if (h >= a.H || c >= a.O) continue;
-    float acc = 0.f;
-    for (int s = 0; s < splits; ++s) acc += G[((int64_t)s * a.H + h) * a.O + c];
-    const float es = a.hash.use_sign == 2 ? (float)elem_sign(a.hash, a.layer, (uint64_t)h, (uint64_t)c) : 1.f;
-    total += a.lambda * (float)sgn[t] * es * acc;
-    any = true;
+  int any = 0;
+  if (live) {
+    // first ranked tile with offset > j - L
+    int64_t lo = 0, hi = nT;
+    while (lo < hi) {
+      const int64_t mid = (lo + hi) >> 1;
+      if (sorted_off[mid] > j - L) hi = mid; else lo = mid + 1;
+    }
+    for (int64_t q = lo + sub; q < nT; q += kGatherLanes) {
+      const int64_t o = sorted_off[q];
+      if (o > j) break;
+      const uint32_t t = order[q];
+      const int64_t p = j - o;
+      const int64_t h = (int64_t)(t / a.nTy) * a.Z1 + p / a.Z2;
+      const int64_t c = (int64_t)(t % a.nTy) * a.Z2 + p % a.Z2;
+      if (h >= a.H || c >= a.O) continue;
+      float acc = 0.f;
+      for (int s = 0; s < splits; ++s) acc += G[((int64_t)s * a.H + h) * a.O + c];
+      const float es = a.hash.use_sign == 2 ? (float)elem_sign(a.hash, a.layer, (uint64_t)h, (uint64_t)c) : 1.f;
+      total += a.lambda * (float)sgn[t] * es * acc;
+      any = 1;
+    }
   }
-  if (any) dM[j] += total;
+#pragma unroll
+  for (int d = kGatherLanes / 2; d >= 1; d >>= 1) {
+    total += __shfl_xor(total, d, 64);
+    any |= __shfl_xor(any, d, 64);
+  }
+  if (live && sub == 0 && any) dM[j] += total;
 }
 
 // Sum the per-split products and scatter them: one workgroup per (tile, block of rows of the tile).
@@ -190,7 +209,7 @@ roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t 
 
   roast_status st = tile_index_launch(a, keys, sgn, s);
   if (st != ROAST_OK) return st;
-  hipLaunchKernelGGL(k_rank_tiles, dim3((unsigned)((nT + 255) / 256)), dim3(256), 0, s, nT, keys, soff, order);
+  hipLaunchKernelGGL(k_rank_tiles, dim3((unsigned)((nT * kRankLanes + 255) / 256)), dim3(256), 0, s, nT, keys, soff, order);
   st = hip_status(hipGetLastError());
   if (st != ROAST_OK) return st;
 
@@ -199,7 +218,7 @@ roast_status dm_det_run(const MMArgs& a, roast_dtype dt, const void* X, int64_t 
   if (st == ROAST_ERR_UNSUPPORTED) st = generic_dm_launch(a, dt, X, ldx, dY, ldy, nullptr, G, splits, s);
   if (st != ROAST_OK) return st;
 
-  hipLaunchKernelGGL(k_dm_gather, dim3((unsigned)((a.m_size + 255) / 256)), dim3(256), 0, s, a, splits, G, soff,
+  hipLaunchKernelGGL(k_dm_gather, dim3((unsigned)((a.m_size * kGatherLanes + 255) / 256)), dim3(256), 0, s, a, splits, G, soff,
                      order, sgn, dM);
   return hip_status(hipGetLastError());
 }
