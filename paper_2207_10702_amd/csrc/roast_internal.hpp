@@ -64,15 +64,18 @@ roast_status generic_dm_launch(const MMArgs& a, roast_dtype dt, const void* X, i
 // ---- ATOMIC mode with a workspace: per-split products to ws, then one scatter (roast_reduce.hip)
 // Number of parts the contraction (over the I rows) of the dM product is cut into when the output
 // has `tiles` workgroup tiles.  The 256 CUs hold one workgroup each, so a launch runs in
-// ceil(tiles*s/256) rounds of ceil(steps/s) 64-row steps plus a fixed cost of about 8 steps per
-// workgroup; the s with the least rounds*(steps + 8) wins, ties go to fewer parts.  A function of
-// the shape only, so results do not depend on the machine's state.
-inline int dm_pick_splits(int64_t tiles, int64_t I) {
+// ceil(tiles*s/256) rounds of ceil(steps/s) 64-row steps (1.38 us each, measured) plus about 8 us
+// per workgroup; with the atomic epilogue every part also adds all `weights` = H*O products into
+// dM, and the chip adds 0.28 M of them per microsecond (weights = 0: no atomic epilogue).  The s
+// with the least estimate wins, ties go to fewer parts.  A function of the shape only, so results
+// do not depend on the machine's state.
+inline int dm_pick_splits(int64_t tiles, int64_t I, int64_t weights) {
   const int64_t steps = (I + 63) / 64;
   int best = 1;
-  int64_t best_cost = INT64_MAX;
+  double best_cost = 1e300;
   for (int s = 1; s <= 16 && (s == 1 || steps / s >= 4); ++s) {
-    const int64_t cost = ((tiles * s + 255) / 256) * ((steps + s - 1) / s + 8);
+    const double cost = (double)((tiles * s + 255) / 256) * ((double)((steps + s - 1) / s) * 1.38 + 8.0) +
+                        (double)s * (double)weights / 0.28e6;
     if (cost < best_cost) { best_cost = cost; best = s; }
   }
   return best;

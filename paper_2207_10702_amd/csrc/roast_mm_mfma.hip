@@ -981,7 +981,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   if (Gws == nullptr && a.hash.use_sign == 2) return ROAST_ERR_UNSUPPORTED;
   if ((cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
   const int64_t tiles = cdiv(a.H, BM) * cdiv(a.O, BN);
-  if (Gws == nullptr) splits = dm_pick_splits(tiles, a.I);
+  if (Gws == nullptr) splits = dm_pick_splits(tiles, a.I, a.H * a.O);
   if (splits < 1 || splits > 65535) return ROAST_ERR_UNSUPPORTED;
   int64_t rows = cdiv(a.I, splits);
   rows = cdiv(rows, BK) * BK;
@@ -1079,7 +1079,7 @@ roast_status x3_mm_bwd_dM(const MMArgs& a, const float* X, int64_t ldx, const fl
   st = split_rows(dY, a.I, a.O, ldy, Gp, s);
   if (st != ROAST_OK) return st;
   const int64_t tiles = cdiv(a.H, kBM) * cdiv(a.O, kBN);
-  const int splits = dm_pick_splits(tiles, 6 * a.I);
+  const int splits = dm_pick_splits(tiles, 6 * a.I, a.H * a.O);
   int64_t rows = cdiv(a.I, splits);
   rows = cdiv(rows, BK) * BK;
   KernArgs p{};

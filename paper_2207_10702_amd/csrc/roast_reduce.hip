@@ -155,7 +155,7 @@ __global__ __launch_bounds__(256) void k_dm_scatter(MMArgs a, int splits, int ro
 // the caller provides a workspace): S*H*O floats.
 int dm_ws_splits(const MMArgs& a) {
   if (a.hash.use_sign == 2) return 0;   // the scatter pass applies one sign per tile
-  const int s = dm_pick_splits(((a.H + 255) / 256) * ((a.O + 127) / 128), a.I);
+  const int s = dm_pick_splits(((a.H + 255) / 256) * ((a.O + 127) / 128), a.I, 0);   // one atomic per weight whatever s
   return s > 1 ? s : 0;               // a single split gains nothing over direct atomics
 }
 
