@@ -347,7 +347,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       for (int q = 0; q < Ctx::DX_LOADS; ++q) {
         const int h = min(n0 + (pt >> 3) + 32 * q, (int)a.H - 1);
         c.dx_ent[q] = h / a.Z1 - n0 / a.Z1;
-        c.dx_rowoff[q] = a.Z2 * (h % a.Z1) + 8 * (pt & 7);
+        c.dx_rowoff[q] = a.Z2 * (h % a.Z1);
       }
     }
     if (MODE == MODE_DM) {
@@ -363,9 +363,11 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       // cover the newest loads as well.
       __builtin_amdgcn_sched_barrier(0);
       if (MODE == MODE_FWD && SHADOW) {
-        const int e = (k0 / a.Z1) * TN + c.fs_yl;
+        // this thread's 4 k-rows lie in one hash tile (Z1 % 4 == 0), not necessarily the step's first
+        const int kabs = k0 + 4 * (pt / Ctx::FS_NG);
+        const int e = (kabs / a.Z1) * TN + c.fs_yl;
         const int64_t off0 = s_off[e];
-        const int64_t rel = off0 + (int64_t)a.Z2 * (k0 % a.Z1 + 4 * (pt / Ctx::FS_NG)) + c.fs_nin;
+        const int64_t rel = off0 + (int64_t)a.Z2 * (kabs % a.Z1) + c.fs_nin;
         // everything added to the tile base is even (Z2 % 8 == 0): the base's parity picks the copy
         const uint16_t* mb = Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);
         r.fw_sgn = s_sgn[e];
@@ -375,8 +377,10 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           r.fs_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
         }
       } else if (MODE == MODE_FWD) {
-        const int e = (k0 / a.Z1) * TN + c.fw_yl;
-        const int64_t rel = s_off[e] + (int64_t)a.Z2 * (k0 % a.Z1 + 8 * (pt / Ctx::FW_NG)) + c.fw_nin;
+        static_assert(Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
+        const int kabs = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
+        const int e = (kabs / a.Z1) * TN + c.fw_yl;
+        const int64_t rel = s_off[e] + (int64_t)a.Z2 * (kabs % a.Z1) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
 #pragma unroll
         for (int b = 0; b < Ctx::FW_BLK; ++b)
@@ -387,7 +391,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
             r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
           }
       } else if (MODE == MODE_DX && SHADOW) {
-        const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
+        // this thread's 8-wide chunk of the contraction axis lies in one hash tile (Z2 % 8 == 0)
+        const int kabs = k0 + 8 * (pt & 7);
+        const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
@@ -398,7 +404,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           r.dx_sgn[q] = s_sgn[e];
         }
       } else if (MODE == MODE_DX) {
-        const int kt = (k0 / a.Z2) * TN, kin = k0 % a.Z2;
+        const int kabs = k0 + 8 * (pt & 7);
+        const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
@@ -903,12 +910,16 @@ roast_status shadow3(const float* M, int64_t m_size, uint16_t* out, hipStream_t 
 }
 
 // (the tile table holds one sign per tile: per-element signs, use_sign == 2, go to the generic kernels)
+// The contraction runs in whole 64-deep steps (H resp. O a multiple of 64); a load thread's block of
+// the weight tile -- 8 rows of the contraction axis (forward), 8 consecutive elements of it (dX) --
+// must lie inside one hash tile, which may be smaller than the step.
 bool mfma_fwd_ok(const MMArgs& a) {
-  return a.hash.use_sign != 2 && a.Z1 % BK == 0 && a.H % a.Z1 == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
+  return a.hash.use_sign != 2 && a.Z1 % 8 == 0 && a.H % BK == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
          a.nTx * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
 }
 bool mfma_dx_ok(const MMArgs& a) {
-  return a.hash.use_sign != 2 && a.Z2 % BK == 0 && a.O % a.Z2 == 0 && a.H % 8 == 0 && a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
+  return a.hash.use_sign != 2 && a.Z2 % 8 == 0 && a.O % BK == 0 && a.H % 8 == 0 &&
+         a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
 }
 
 }  // namespace

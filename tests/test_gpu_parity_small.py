@@ -155,6 +155,10 @@ MFMA_SHAPES = [
     (300, 128, 240, 64, 12, 20000),     # forward on the MFMA path, but tiles too narrow for the 8-column shadow reads
     (520, 192, 136, 64, 8, 7000),       # 17 hash tiles under one 128-column block; ragged last block
     (257, 64, 128, 64, 128, 8193),      # one row past a 256-row block; |M| = one tile + 1: two offsets only
+    (300, 256, 256, 32, 32, 4096),      # hash tiles smaller than the 64-deep step (config 1's tiling)
+    (513, 192, 136, 16, 8, 7000),       # 8- and 16-wide tiles, several per step and per block
+    (260, 128, 192, 8, 64, 9000),       # 8 tile rows per step (forward), full-width tiles for dX
+    (300, 192, 128, 48, 24, 5000),      # tiles that do not divide the step: rows 48, columns 24
     (8000, 128, 3072, 64, 64, 30000),   # wide output, 31.25 row blocks (three rounds of workgroups), ragged rows
     (7950, 3072, 128, 64, 64, 30000),   # wide input gradient, ragged rows
 ]
