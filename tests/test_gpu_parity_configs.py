@@ -75,7 +75,22 @@ def test_cfg1_single_layer_fp32_complete(roast):
     X, dY = inp.X[l.name].astype(np.float64), inp.dY[l.name].astype(np.float64)
     assert rel_err(to_host_f64(Y), oracle.mm_fwd(X, W)) <= F32_TOL
     assert rel_err(to_host_f64(dX), oracle.mm_bwd_dx(dY, W)) <= F32_TOL
-    assert rel_err(to_host_f64(dM), oracle.mm_bwd_dm(inp.hash, l.layer_id, cfg.Z1, cfg.Z2, cfg.m_size, cfg.lam, X, dY)) <= F32_TOL
+    ref_dM = oracle.mm_bwd_dm(inp.hash, l.layer_id, cfg.Z1, cfg.Z2, cfg.m_size, cfg.lam, X, dY)
+    assert rel_err(to_host_f64(dM), ref_dM) <= F32_TOL
+    # the configuration bench.py --workload cfg1_single_f32 times: the same calls with their workspaces
+    # (fp32 on the matrix cores; the 32x32 hash tiles are half the kernel's contraction step)
+    sizes = (roast.roast_mm_fwd_workspace(d, torch.float32, cfg.I), roast.roast_mm_bwd_dx_workspace(d, torch.float32, cfg.I),
+             roast.roast_mm_bwd_dM_workspace_f32(d, cfg.I))
+    assert min(sizes) > 0
+    ws = torch.empty(max(sizes), dtype=torch.uint8, device="cuda")
+    planes = roast.roast_m_planes_bf16(Md)
+    Yw = roast.roast_mm_fwd(d, Xd, Md, M_bf16=planes, ws=ws)
+    dXw = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=planes, ws=ws)
+    dMw = torch.zeros(cfg.m_size, dtype=torch.float32, device="cuda")
+    roast.roast_mm_bwd_dM(d, Xd, dYd, dMw, roast.ROAST_REDUCE_ATOMIC, ws)
+    assert rel_err(to_host_f64(Yw), oracle.mm_fwd(X, W)) <= F32_TOL
+    assert rel_err(to_host_f64(dXw), oracle.mm_bwd_dx(dY, W)) <= F32_TOL
+    assert rel_err(to_host_f64(dMw), ref_dM) <= F32_TOL
 
 
 # ------------------------------------------------------------------ config 2 (chained FFN pair, bf16)
