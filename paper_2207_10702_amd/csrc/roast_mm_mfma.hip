@@ -690,7 +690,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     for (int i = 0; i < MI; ++i)
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
-        const int hb = m0 + wm * WTM + i * 32;      // block origin: inside one hash tile (Z1, Z2 % 32 == 0)
+        const int hb = m0 + wm * WTM + i * 32;      // block origin
         const int ob = n0 + wn * WTN + j * 32;
         if (hb >= (int)a.H || ob >= (int)a.O) continue;
         if (p.G) {
@@ -701,13 +701,18 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
             if (hb + r < (int)a.H && ob + lc < (int)a.O) g[(int64_t)r * a.O] = acc[i][j][e];
           }
         } else {
-          const int ent = (hb / a.Z1 - m0 / a.Z1) * TN + (ob / a.Z2 - n0 / a.Z2);
-          const float sc = a.lambda * s_sgn[ent];
-          float* d = p.dM + s_off[ent] + (int64_t)a.Z2 * (hb % a.Z1) + (ob % a.Z2) + lc;
+          // a lane's four consecutive rows (e % 4) share a hash tile (Z1 % 4 == 0); its column has
+          // its own tile column: one table lookup per group of four values
+          const int o = ob + lc, yl = o / a.Z2 - n0 / a.Z2, oin = o % a.Z2;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int r = 8 * (e >> 2) + lr + (e & 3);
-            if (hb + r < (int)a.H && ob + lc < (int)a.O) unsafeAtomicAdd(d + (int64_t)r * a.Z2, sc * acc[i][j][e]);
+          for (int q = 0; q < 4; ++q) {
+            const int h = hb + 8 * q + lr;
+            const int ent = (h / a.Z1 - m0 / a.Z1) * TN + yl;
+            const float sc = a.lambda * s_sgn[ent];
+            float* d = p.dM + s_off[ent] + (int64_t)a.Z2 * (h % a.Z1) + oin;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (h + r < (int)a.H && o < (int)a.O) unsafeAtomicAdd(d + (int64_t)r * a.Z2, sc * acc[i][j][4 * q + r]);
           }
         }
       }
@@ -985,7 +990,7 @@ static void uneven_parts(int64_t I, int splits, int* begin) {
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
                             float* Gws, int splits, hipStream_t s) {
   constexpr int BM = 256, BN = 128;
-  if (a.Z1 % 32 != 0 || a.Z2 % 32 != 0 || a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
+  if (a.Z1 % 4 != 0 || a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
       !aligned16(X) || !aligned16(dY) || a.H < BM / 32 || a.O < BN / 32)
     return ROAST_ERR_UNSUPPORTED;
   // the atomic epilogue applies one sign per tile; raw products for the deterministic reduction are sign-free
@@ -1011,7 +1016,7 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
 bool x3_fwd_ok(const MMArgs& a) { return mfma_fwd_ok(a) && a.Z2 % 8 == 0 && a.O % 4 == 0; }
 bool x3_dx_ok(const MMArgs& a) { return mfma_dx_ok(a) && a.H % 4 == 0; }
 bool x3_dm_ok(const MMArgs& a) {
-  return a.hash.use_sign != 2 && a.Z1 % 32 == 0 && a.Z2 % 32 == 0 && a.H % 8 == 0 && a.O % 8 == 0 && a.H >= kBM / 32 && a.O >= kBN / 32 &&
+  return a.hash.use_sign != 2 && a.Z1 % 4 == 0 && a.H % 8 == 0 && a.O % 8 == 0 && a.H >= kBM / 32 && a.O >= kBN / 32 &&
          (cdiv(kBM, a.Z1) + 1) * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
 }
 int x3_fwd_splits(const MMArgs& a) { return mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), 6 * a.H); }
