@@ -205,7 +205,9 @@ struct RegSet {
 // of nine plane products, of which the six of weight >= 2^-16 are kept: (hi,hi) (hi,mid) (mid,hi)
 // (hi,lo) (lo,hi) (mid,mid).  What is dropped is below 2^-23 of |x||w|, the accumulation is the
 // usual fp32 one.  The contraction loop simply runs six times as many steps: step = 6*kq + pair.
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false>
+// RAGK: the contraction length of forward / dX is a multiple of 8 but not of 64 (a separate
+// instantiation: the extra selects in the load waves cost the regular kernels 15 %).
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false>
 __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p) {
   static_assert(!X3 || SHADOW || MODE == MODE_DM, "the plane kernels read the weight planes, not fp32 M");
   constexpr int NC = WGM * WGN;                  // consumer waves
@@ -325,12 +327,21 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     auto dma_issue = [&](int step) {
       if constexpr (ADMA) {
         const int st = min(step, nsteps - 1);
-        const int64_t k0 = step_k0(st) + (X3 ? step_asel(st) * p.a_plane : 0);
+        const int kk = step_k0(st);
+        const int64_t pl = X3 ? step_asel(st) * p.a_plane : 0;
         char* dst = a_stage(step) + (wave - NC) * (BM / 4) * 128;
+        // A ragged contraction length (a multiple of 8, not of 64): the 16-byte pieces of the last
+        // step that lie beyond it are fetched from the start of the row instead (any finite value
+        // will do: the weight rows they meet are staged as zeros).  ch(q) = ch(0) ^ q, see above.
+        const bool ragged = RAGK && kk + BK > k_end;
+        const int ch0 = (lane ^ (lane >> 3)) & 7;
 #pragma unroll
-        for (int q = 0; q < Ctx::A_LOADS; ++q)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(c.a_ptr[q] + k0),
+        for (int q = 0; q < Ctx::A_LOADS; ++q) {
+          const int ch8 = 8 * (ch0 ^ (q & 7));
+          const int64_t koff = (RAGK && ragged && kk + ch8 >= k_end) ? pl - ch8 : pl + kk;
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(c.a_ptr[q] + koff),
                                            (__attribute__((address_space(3))) void*)(dst + q * 1024), 16, 0, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -364,7 +375,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       __builtin_amdgcn_sched_barrier(0);
       if (MODE == MODE_FWD && SHADOW) {
         // this thread's 4 k-rows lie in one hash tile (Z1 % 4 == 0), not necessarily the step's first
-        const int kabs = k0 + 4 * (pt / Ctx::FS_NG);
+        const int kraw = k0 + 4 * (pt / Ctx::FS_NG);
+        const int kabs = RAGK ? min(kraw, k_end - 4) : kraw;   // rows beyond a ragged contraction length: zeros below
         const int e = (kabs / a.Z1) * TN + c.fs_yl;
         const int64_t off0 = s_off[e];
         const int64_t rel = off0 + (int64_t)a.Z2 * (kabs % a.Z1) + c.fs_nin;
@@ -374,11 +386,12 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const h8a m = *reinterpret_cast<const h8a*>(mb + rel + (int64_t)q * a.Z2);
-          r.fs_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
+          r.fs_reg[q] = (!RAGK || kraw < k_end) ? uint4v{m.v[0], m.v[1], m.v[2], m.v[3]} : uint4v{0u, 0u, 0u, 0u};
         }
       } else if (MODE == MODE_FWD) {
         static_assert(Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
-        const int kabs = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
+        const int kraw = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
+        const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
         const int e = (kabs / a.Z1) * TN + c.fw_yl;
         const int64_t rel = s_off[e] + (int64_t)a.Z2 * (kabs % a.Z1) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
@@ -388,11 +401,12 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           for (int q = 0; q < 8; ++q) {
             const int64_t at = rel + (int64_t)(8 * Ctx::FW_KBS * b + q) * a.Z2;
             const f4u m = *reinterpret_cast<const f4u*>(p.M + at);
-            r.fw_reg[b * 8 + q] = floatx4{m.v[0], m.v[1], m.v[2], m.v[3]};
+            r.fw_reg[b * 8 + q] = (!RAGK || kraw < k_end) ? floatx4{m.v[0], m.v[1], m.v[2], m.v[3]} : floatx4{0.f, 0.f, 0.f, 0.f};
           }
       } else if (MODE == MODE_DX && SHADOW) {
         // this thread's 8-wide chunk of the contraction axis lies in one hash tile (Z2 % 8 == 0)
-        const int kabs = k0 + 8 * (pt & 7);
+        const int kraw = k0 + 8 * (pt & 7);
+        const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;   // chunks beyond a ragged contraction length: zeros
         const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
@@ -400,20 +414,22 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           const int64_t off0 = s_off[e];
           const uint16_t* mb = Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);     // row offsets are even (Z2 % 8 == 0)
           const h8a m = *reinterpret_cast<const h8a*>(mb + off0 + c.dx_rowoff[q] + kin);
-          r.ds_reg[q] = uint4v{m.v[0], m.v[1], m.v[2], m.v[3]};
+          r.ds_reg[q] = (!RAGK || kraw < k_end) ? uint4v{m.v[0], m.v[1], m.v[2], m.v[3]} : uint4v{0u, 0u, 0u, 0u};
           r.dx_sgn[q] = s_sgn[e];
         }
       } else if (MODE == MODE_DX) {
-        const int kabs = k0 + 8 * (pt & 7);
+        const int kraw = k0 + 8 * (pt & 7);
+        const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
         const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
+        const float keep = (!RAGK || kraw < k_end) ? 1.f : 0.f;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
           const float* src = p.M + s_off[e] + c.dx_rowoff[q] + kin;
           const f4u m0v = *reinterpret_cast<const f4u*>(src);
           const f4u m1v = *reinterpret_cast<const f4u*>(src + 4);
-          r.dx_reg[2 * q] = floatx4{m0v.v[0], m0v.v[1], m0v.v[2], m0v.v[3]};
-          r.dx_reg[2 * q + 1] = floatx4{m1v.v[0], m1v.v[1], m1v.v[2], m1v.v[3]};
+          r.dx_reg[2 * q] = floatx4{keep * m0v.v[0], keep * m0v.v[1], keep * m0v.v[2], keep * m0v.v[3]};
+          r.dx_reg[2 * q + 1] = floatx4{keep * m1v.v[0], keep * m1v.v[1], keep * m1v.v[2], keep * m1v.v[3]};
           r.dx_sgn[q] = s_sgn[e];
         }
       }
@@ -722,7 +738,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
 template <int MODE, int BM, int BN>
 constexpr int smem_bytes() { return ((MODE != MODE_DM ? 3 : 2) * BM + 2 * BN) * 128 + kMaxTable * 12; }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false>
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false>
 roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
@@ -732,12 +748,13 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   static_assert(smem <= 160 * 1024, "LDS budget");
   static std::atomic<bool> configured{false};   // per instantiation and process; a race between host threads only repeats the call
   if (!configured.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
     configured.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3>), grid, dim3((WGM * WGN + 8) * 64), smem, s, p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK>), grid, dim3((WGM * WGN + 8) * 64), smem, s,
+                     p);
   return hip_status(hipGetLastError());
 }
 
@@ -915,15 +932,15 @@ roast_status shadow3(const float* M, int64_t m_size, uint16_t* out, hipStream_t 
 }
 
 // (the tile table holds one sign per tile: per-element signs, use_sign == 2, go to the generic kernels)
-// The contraction runs in whole 64-deep steps (H resp. O a multiple of 64); a load thread's block of
-// the weight tile -- 8 rows of the contraction axis (forward), 8 consecutive elements of it (dX) --
+// The contraction runs in 64-deep steps; its length (H resp. O) only has to be a multiple of 8: the
+// last step's surplus is staged as zero weights.  A load thread's block of the weight tile -- 8 rows of the contraction axis (forward), 8 consecutive elements of it (dX) --
 // must lie inside one hash tile, which may be smaller than the step.
 bool mfma_fwd_ok(const MMArgs& a) {
-  return a.hash.use_sign != 2 && a.Z1 % 8 == 0 && a.H % BK == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
+  return a.hash.use_sign != 2 && a.Z1 % 8 == 0 && a.H % 8 == 0 && a.Z2 % 4 == 0 && a.O % 8 == 0 &&
          a.nTx * (cdiv(kBN, a.Z2) + 1) <= kMaxTable;
 }
 bool mfma_dx_ok(const MMArgs& a) {
-  return a.hash.use_sign != 2 && a.Z2 % 8 == 0 && a.O % BK == 0 && a.H % 8 == 0 &&
+  return a.hash.use_sign != 2 && a.Z2 % 8 == 0 && a.O % 8 == 0 && a.H % 8 == 0 &&
          a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
 }
 
@@ -947,8 +964,13 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.I, BM), 1);
   split_setup(&p, &grid, a.H, mfma_fwd_splits(a), ws);
   // the shadow is read in 8-column pieces, which must not straddle tiles
-  const roast_status st = (M_bf16 && a.Z2 % 8 == 0) ? launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s)
-                                                    : launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
+  const bool shadow = M_bf16 && a.Z2 % 8 == 0;
+  roast_status st;
+  if (a.H % BK != 0)
+    st = shadow ? launch<MODE_FWD, BM, BN, 4, 2, true, false, true>(p, grid, s)
+                : launch<MODE_FWD, BM, BN, 4, 2, false, false, true>(p, grid, s);
+  else
+    st = shadow ? launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s) : launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
@@ -962,8 +984,12 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   p.mb_stride = shadow_stride(a.m_size); p.C = (uint16_t*)dX; p.ldc = ldx;
   dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   split_setup(&p, &grid, a.O, mfma_dx_splits(a), ws);
-  const roast_status st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s)
-                                 : launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
+  roast_status st;
+  if (a.O % BK != 0)
+    st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true, false, true>(p, grid, s)
+                : launch<MODE_DX, BM, BN, 4, 2, false, false, true>(p, grid, s);
+  else
+    st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s) : launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 
@@ -1059,7 +1085,8 @@ roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float
   p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = Y; p.ldc = ldy;
   dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.I, kBM), 1);
   split_setup(&p, &grid, a.H, x3_fwd_splits(a), parts);
-  st = launch<MODE_FWD, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  st = a.H % BK != 0 ? launch<MODE_FWD, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
+                     : launch<MODE_FWD, kBM, kBN, 4, 2, true, true>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
@@ -1080,7 +1107,8 @@ roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const f
   p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = dX; p.ldc = ldx;
   dim3 grid((unsigned)cdiv(a.H, kBN), (unsigned)cdiv(a.I, kBM), 1);
   split_setup(&p, &grid, a.O, x3_dx_splits(a), parts);
-  st = launch<MODE_DX, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  st = a.O % BK != 0 ? launch<MODE_DX, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
+                     : launch<MODE_DX, kBM, kBN, 4, 2, true, true>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 

@@ -18,7 +18,7 @@ SHAPES = [
     (300, 128, 320, 64, 64, 20000),
     (513, 256, 128, 128, 128, 40000),      # one row past two 256-row blocks
     (1000, 64, 576, 64, 64, 4096),         # |M| == one tile
-    (700, 640, 72, 64, 8, 5000),           # narrow hash tiles, ragged columns (dX falls back: O is not a multiple of 64)
+    (700, 640, 72, 64, 8, 5000),           # narrow hash tiles, ragged columns; dX contracts over 72 = 64 + 8
     (300, 256, 256, 32, 32, 4096),         # hash tiles half the 64-deep step (config 1's tiling)
     (260, 128, 192, 16, 8, 9000),          # 16 x 8 tiles, several per 32 x 32 accumulator block
     (64, 2048, 256, 64, 64, 50000),        # small batch: split contraction, fp32 partial sums
@@ -51,7 +51,7 @@ def test_f32_plane_products_match_oracle(roast, shape, pad):
     nx = roast.roast_mm_bwd_dx_workspace(d, torch.float32, I)
     nm = roast.roast_mm_bwd_dM_workspace_f32(d, I)
     assert nf > 0                                    # every shape here is covered by the forward kernel
-    assert (nx > 0) == (Z2 % 8 == 0 and O % 64 == 0) and (nm > 0) == (Z1 % 4 == 0)
+    assert (nx > 0) == (Z2 % 8 == 0) and (nm > 0) == (Z1 % 4 == 0)
     wf, wx, wm = ws_tensor(nf), ws_tensor(nx), ws_tensor(nm)
     outs = []
     planes = roast.roast_m_planes_bf16(Md)             # made once, or rebuilt per call in the workspace: same bits

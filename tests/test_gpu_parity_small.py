@@ -159,6 +159,8 @@ MFMA_SHAPES = [
     (513, 192, 136, 16, 8, 7000),       # 8- and 16-wide tiles, several per step and per block
     (260, 128, 192, 8, 64, 9000),       # 8 tile rows per step (forward), full-width tiles for dX
     (300, 192, 128, 48, 24, 5000),      # tiles that do not divide the step: rows 48, columns 24
+    (300, 200, 136, 8, 8, 9000),        # contraction lengths that are multiples of 8 only: 200 (forward), 136 (dX)
+    (520, 72, 1000, 24, 40, 30000),     # one ragged step (72), 15.6 steps (1000)
     (300, 128, 240, 8, 12, 20000),      # forward from fp32 M (no shadow reads: Z2 % 8 != 0), 8 tile rows per step
     (400, 264, 136, 20, 1, 6000),       # dM on the matrix cores with 20 x 1 tiles (forward / dX generic)
     (1030, 128, 128, 4, 4, 3000),       # 4 x 4 tiles: dM on the matrix cores, 1089 tiles under one block
