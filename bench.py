@@ -177,11 +177,11 @@ def bench_dim_sweep(args, roast, wl, torch, np):
     """Square Dim x Dim ROAST-MM layers at batch 512 (the shape family of the paper's Table 1 and
     Appendix B), |M| from 4 MB to 512 MB, bf16 with 64x64 tiles: forward, dX, dM and the optimizer
     step, each timed alone, with the vendor dense bf16 GEMM of the same shape beside them.  The
-    printed Dim 8096 is run as 8192 (a multiple of the tile)."""
+    printed Dim 8096 is run as printed (126.5 tiles per side: ragged last tile and last contraction step)."""
     I, Z = 512, 64
     f32 = args.dtype == "f32"
     tdt = torch.float32 if f32 else torch.bfloat16
-    dims = [512, 1024, 2048, 4096, 8192, 10240, 20480]
+    dims = [512, 1024, 2048, 4096, 8096, 10240, 20480]
     m_sizes = [1 << 20, 16 << 20, 128 << 20]
     g = torch.Generator(device="cuda").manual_seed(2207)
     hp = wl.draw_hash(np.random.default_rng(10702), use_sign=True, align=1)
