@@ -25,6 +25,12 @@
  *   - Errors are return codes; nothing is launched when a call returns non-zero, except
  *     ROAST_ERR_HIP which reports a launch failure from the runtime.
  *   - Sizes of zero rows (I == 0, N == 0) are a successful no-op.
+ *   - Every shape is accepted; which kernels run is a matter of speed, never of results beyond the
+ *     stated tolerances.  The matrix-core kernels take ROAST_BF16 calls (and ROAST_F32 calls that
+ *     come with a workspace, see roast_mm_fwd_ws) with 16-byte aligned pointers, leading dimensions
+ *     that are multiples of 8, H and O multiples of 8, and tiles with Z1 % 8 == 0 and Z2 % 4 == 0
+ *     (forward), Z2 % 8 == 0 (dX), Z1 % 4 == 0 (dM), per-block sign; the lookup kernels are fastest
+ *     with Z % 4 == 0, D % Z == 0 and |M| < 2^31.  Everything else runs on generic kernels.
  */
 #ifndef ROAST_H
 #define ROAST_H
