@@ -62,7 +62,8 @@ struct __attribute__((packed, aligned(4))) h8a {
 };
 
 constexpr int BK = 64;
-constexpr int kBM = 256, kBN = 128;   // workgroup tile of every kernel here
+constexpr int kBM = 256, kBN = 128;   // workgroup tile of every kernel here ...
+constexpr int kBNarrow = 96;          // ... but the narrow forward / dX blocks
 constexpr int kMaxTable = 2048; // tile-table entries a workgroup may need
 enum { MODE_FWD = 0, MODE_DX = 1, MODE_DM = 2 };
 
@@ -177,7 +178,7 @@ struct ProdCtx {
   int fw_yl, fw_nin;
   // FWD from the bf16 shadow: 4(k) x 8(n) bf16 blocks (16-byte loads); thread -> column group ptid % FS_NG, k-block ptid / FS_NG
   static constexpr int FS_NG = BN / 8;
-  static_assert(256 / FS_NG * 4 == 64, "one 4 x 8 block per producer thread covers the 64-deep step");
+  static_assert(FS_NG <= 16, "at most one 4 x 8 block per producer thread and 64-deep step (threads beyond 16 * FS_NG idle)");
   int fs_yl, fs_nin;
   // DX, B operand: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
   int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
@@ -375,7 +376,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       __builtin_amdgcn_sched_barrier(0);
       if (MODE == MODE_FWD && SHADOW) {
         // this thread's 4 k-rows lie in one hash tile (Z1 % 4 == 0), not necessarily the step's first
-        const int kraw = k0 + 4 * (pt / Ctx::FS_NG);
+        // (a block narrower than 128 columns leaves the threads beyond 16 * FS_NG without work:
+        // they repeat the last row block's loads and store nothing)
+        const int kraw = k0 + 4 * min(pt / Ctx::FS_NG, 15);
         const int kabs = RAGK ? min(kraw, k_end - 4) : kraw;   // rows beyond a ragged contraction length: zeros below
         const int e = (kabs / a.Z1) * TN + c.fs_yl;
         const int64_t off0 = s_off[e];
@@ -389,7 +392,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           r.fs_reg[q] = (!RAGK || kraw < k_end) ? uint4v{m.v[0], m.v[1], m.v[2], m.v[3]} : uint4v{0u, 0u, 0u, 0u};
         }
       } else if (MODE == MODE_FWD) {
-        static_assert(Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
+        static_assert(MODE != MODE_FWD || SHADOW || Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
         const int kraw = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
         const int e = (kabs / a.Z1) * TN + c.fw_yl;
@@ -444,6 +447,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         const int kb4 = pt / Ctx::FS_NG;            // k = 4*kb4 .. +3: half a 16-byte chunk per column
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) {
+          if (Ctx::FS_NG < 16 && kb4 >= 16) break;
           const uint32_t sel = (cc & 1) ? 0x07060302u : 0x05040100u;
           const uint2v o = {__builtin_amdgcn_perm(r.fs_reg[1][cc >> 1], r.fs_reg[0][cc >> 1], sel) ^ flip,
                             __builtin_amdgcn_perm(r.fs_reg[3][cc >> 1], r.fs_reg[2][cc >> 1], sel) ^ flip};
@@ -668,8 +672,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
             *reinterpret_cast<float4v*>(ebuf + (lane & 31) * ES + (j * 32 + 8 * q + 4 * (lane >> 5)) * 4) = w;
           }
 #pragma unroll
-        for (int it = 0; it < 32 / RPI; ++it) {
+        for (int it = 0; it < (32 + RPI - 1) / RPI; ++it) {
           const int r = it * RPI + lane / CPR, cc = lane % CPR;
+          if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;   // (only when CPR does not divide 64)
           const float4v v = *reinterpret_cast<const float4v*>(ebuf + r * ES + cc * 16);
           const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 4;
           if (row < Mdim && col < Ndim) *reinterpret_cast<float4v*>(part + row * ldp + col) = v;
@@ -692,8 +697,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         }
       // same wave wrote and reads: LDS operations of one wave complete in order
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < (32 + RPI - 1) / RPI; ++it) {
         const int r = it * RPI + lane / CPR, cc = lane % CPR;
+        if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;     // (only when CPR does not divide 64)
         const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + cc * 16);
         const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 8;
         if (row < Mdim && col < Ndim) *reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col) = v;
@@ -966,7 +972,13 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   // the shadow is read in 8-column pieces, which must not straddle tiles
   const bool shadow = M_bf16 && a.Z2 % 8 == 0;
   roast_status st;
-  if (a.H % BK != 0)
+  const int64_t rb = cdiv(a.I, BM);             // narrow blocks: see mfma_mm_bwd_dx
+  const bool narrow = shadow && a.H % BK == 0 && grid.z == 1 &&
+                      cdiv(rb * cdiv(a.O, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(a.O, BN), 256) * BN;
+  if (narrow) {
+    grid.x = (unsigned)cdiv(a.O, kBNarrow);
+    st = launch<MODE_FWD, BM, kBNarrow, 8, 1, true>(p, grid, s);
+  } else if (a.H % BK != 0)
     st = shadow ? launch<MODE_FWD, BM, BN, 4, 2, true, false, true>(p, grid, s)
                 : launch<MODE_FWD, BM, BN, 4, 2, false, false, true>(p, grid, s);
   else
@@ -985,7 +997,15 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   split_setup(&p, &grid, a.O, mfma_dx_splits(a), ws);
   roast_status st;
-  if (a.O % BK != 0)
+  // A narrower block (256 x 96, eight 32 x 96 consumer tiles) when it fills the 256 CUs in fewer or
+  // shorter rounds: 8192 x 768 outputs are 192 blocks of 128 columns but exactly 256 of 96.
+  const int64_t rb = cdiv(a.I, BM);
+  const bool narrow = M_bf16 && a.O % BK == 0 && grid.z == 1 &&
+                      cdiv(rb * cdiv(a.H, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(a.H, BN), 256) * BN;
+  if (narrow) {
+    grid.x = (unsigned)cdiv(a.H, kBNarrow);
+    st = launch<MODE_DX, BM, kBNarrow, 8, 1, true>(p, grid, s);
+  } else if (a.O % BK != 0)
     st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true, false, true>(p, grid, s)
                 : launch<MODE_DX, BM, BN, 4, 2, false, false, true>(p, grid, s);
   else

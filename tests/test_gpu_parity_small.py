@@ -166,6 +166,8 @@ MFMA_SHAPES = [
     (1030, 128, 128, 4, 4, 3000),       # 4 x 4 tiles: dM on the matrix cores, 1089 tiles under one block
     (8000, 128, 3072, 64, 64, 30000),   # wide output, 31.25 row blocks (three rounds of workgroups), ragged rows
     (7950, 3072, 128, 64, 64, 30000),   # wide input gradient, ragged rows
+    (520, 256, 768, 64, 64, 20000),     # 96-column blocks (chosen when they fill the CUs better): 8 along O, 2.67 along H
+    (300, 448, 200, 64, 8, 9000),       # 96-column blocks with a ragged last block (200 = 96 + 96 + 8; 448 = 4.67 x 96)
 ]
 
 
