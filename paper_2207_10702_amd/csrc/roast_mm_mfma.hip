@@ -265,11 +265,13 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   auto step_asel = [&](int step) { return X3 ? (0x120100 >> (4 * (step % 6))) & 3 : 0; };   // plane of A
   auto step_bsel = [&](int step) { return X3 ? (0x102010 >> (4 * (step % 6))) & 3 : 0; };   // plane of B / M
 
-  // ---- tile table (all threads)
+  // ---- tile table (all threads but the waves that only issue direct-to-LDS loads: those have the
+  // first step's loads on their way while the others hash, and meet them at the barrier below)
   // FWD: entry [kt * TN + yl] for tile (x = kt, y = n0/Z2 + yl), TN = tiles spanned by BN along O
   // DX : entry [kt * TN + xl] for tile (x = n0/Z1 + xl, y = kt), TN = tiles spanned by BN along H
   // DM : entry [xl * TN + yl] for tile (x = m0/Z1 + xl, y = n0/Z2 + yl)
   int TN = 1;
+  const bool dma_wave = ADMA && wave >= NC && wave < NC + 4;
   {
     int x0 = 0, y0 = 0, cnt = 0;
     if (MODE == MODE_FWD) {
@@ -285,7 +287,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
       cnt = ((min(m0 + BM, (int)a.H) - 1) / a.Z1 - x0 + 1) * TN;
     }
-    for (int e = tid; e < cnt; e += NT) {
+    constexpr int NB = ADMA ? NT - 256 : NT;     // threads that build the table
+    const int bi = (ADMA && wave >= NC) ? tid - 256 : tid;
+    for (int e = dma_wave ? cnt : bi; e < cnt; e += NB) {
       uint64_t x, y;
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
       else if (MODE == MODE_DX) { y = e / TN; x = x0 + e % TN; }
@@ -294,7 +298,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       s_sgn[e] = (float)block_sign(a.hash, a.layer, x, y);
     }
   }
-  __syncthreads();
+  if (!dma_wave) __syncthreads();
 
   if (producer) {
     // =========================================================================== producer waves
@@ -538,6 +542,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     if (a_producer) {
       // iteration s: fetch A(s+1), then wait until A(s) has landed (only A(s+1) is younger)
       if (nsteps > 0) dma_issue(0);
+      __builtin_amdgcn_s_barrier();                      // the other waves' barrier behind the tile table
       for (int s = 0; s < nsteps; ++s) {
         dma_issue(s + 1);
         __builtin_amdgcn_s_waitcnt(vmcnt_only(Ctx::A_LOADS));
