@@ -322,6 +322,7 @@ constexpr int kSeg = 8192;          // chunks per accumulate workgroup
 constexpr int kMaxBuckets = 2048;
 constexpr int kMaxR = 8192;         // largest bucket (slots), its fp64 LDS image is 64 KiB
 constexpr int kRouteItems = 4096;   // chunks per route workgroup (lookups per workgroup = kRouteItems / C)
+constexpr int kRouteThreads = 256;
 
 struct BucketPlan {
   bool ok;
@@ -454,7 +455,7 @@ __global__ __launch_bounds__(256) void k_embed_fixed_finish(int64_t m_size, floa
 
 // entry = (chunk number g, key); key = offset | (negative sign << 31)
 template <bool FIXED>
-__global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, int nb, uint32_t cap, int walk,
+__global__ __launch_bounds__(kRouteThreads) void k_embed_route(EmbedArgs a, int r_log2, int nb, uint32_t cap, int walk,
                                                      const int64_t* __restrict__ rows,
                                                      const uint32_t* __restrict__ tables, uint32_t* __restrict__ cursor,
                                                      uint2* __restrict__ list, const float* __restrict__ dOut,
@@ -468,12 +469,15 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
   uint16_t* s_pos = reinterpret_cast<uint16_t*>(s_key + items);   // [items] rank inside (workgroup, bucket)
   uint32_t* hist = s_key + items + items / 2;                      // [nb]  chunks of this workgroup per bucket
   uint32_t* gbase = hist + nb;                                     // [nb]  reserved position in the bucket's global list
-  uint32_t* s_src = gbase + nb;                                    // [rows_wg] gradient row of each lookup (pooled calls only)
-  for (int i = threadIdx.x; i < nb; i += 256) hist[i] = 0u;
+  uint32_t* pre = gbase + nb;                                      // [nb]  chunks of this workgroup in the buckets before
+  uint16_t* s_ord = reinterpret_cast<uint16_t*>(pre + nb);         // [items] chunk index by (bucket, rank)
+  uint32_t* s_src = reinterpret_cast<uint32_t*>(s_ord + items);    // [rows_wg] gradient row of each lookup (pooled calls only)
+  __shared__ uint32_t s_part[kRouteThreads];
+  for (int i = threadIdx.x; i < nb; i += kRouteThreads) hist[i] = 0u;
   __syncthreads();
   const int64_t n0 = (int64_t)blockIdx.x * rows_wg;
   const int rows_here = (int)min((int64_t)rows_wg, a.N - n0);
-  for (int q = threadIdx.x; q < rows_here; q += 256) {
+  for (int q = threadIdx.x; q < rows_here; q += kRouteThreads) {
     const int64_t n = n0 + q;
     if (a.bag_off) s_src[q] = (uint32_t)bag_of(a.bag_off, a.B, n);
     for_each_chunk(a, walk != 0, tables[n], (uint64_t)rows[n], [&](int64_t c, int64_t off, int sgn) {
@@ -483,12 +487,43 @@ __global__ __launch_bounds__(256) void k_embed_route(EmbedArgs a, int r_log2, in
   }
   __syncthreads();
   // one global add per (workgroup, bucket) reserves that many consecutive list slots
-  for (int i = threadIdx.x; i < nb; i += 256) gbase[i] = hist[i] ? atomicAdd(&cursor[i], hist[i]) : 0u;
+  for (int i = threadIdx.x; i < nb; i += kRouteThreads) gbase[i] = hist[i] ? atomicAdd(&cursor[i], hist[i]) : 0u;
+  // exclusive prefix of the histogram: where the workgroup's chunks of bucket b start when ordered
+  // by (bucket, rank)
+  {
+    const int per = (nb + kRouteThreads - 1) / kRouteThreads;
+    uint32_t sum = 0;
+    for (int j = 0; j < per; ++j) {
+      const int idx = threadIdx.x * per + j;
+      if (idx < nb) sum += hist[idx];
+    }
+    s_part[threadIdx.x] = sum;
+    __syncthreads();
+    for (int off = 1; off < kRouteThreads; off <<= 1) {
+      const uint32_t v = (int)threadIdx.x >= off ? s_part[threadIdx.x - off] : 0u;
+      __syncthreads();
+      s_part[threadIdx.x] += v;
+      __syncthreads();
+    }
+    uint32_t run = s_part[threadIdx.x] - sum;
+    for (int j = 0; j < per; ++j) {
+      const int idx = threadIdx.x * per + j;
+      if (idx < nb) { pre[idx] = run; run += hist[idx]; }
+    }
+  }
   __syncthreads();
   // every chunk knows its bucket and its rank inside (workgroup, bucket): that is its list slot.
-  // The entries of one run land next to each other, L2 merges them into whole lines.
+  // The chunks are written out in (bucket, rank) order, so that consecutive threads store to
+  // consecutive list slots of one run (a store instruction then touches a handful of lines instead
+  // of 64: scattered 8-byte stores were what this kernel spent its time on).
   const int n_here = rows_here * C;
-  for (int i = threadIdx.x; i < n_here; i += 256) {
+  for (int i = threadIdx.x; i < n_here; i += kRouteThreads) {
+    const uint32_t b = (s_key[i] & 0x7fffffffu) >> r_log2;
+    s_ord[pre[b] + s_pos[i]] = (uint16_t)i;
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < n_here; t += kRouteThreads) {
+    const int i = s_ord[t];
     const uint32_t key = s_key[i];
     const uint32_t b = (key & 0x7fffffffu) >> r_log2;
     const uint32_t pos = gbase[b] + s_pos[i];
@@ -639,15 +674,15 @@ roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* 
   uint2* list = (uint2*)(base + p.list_off);
   hipLaunchKernelGGL(k_embed_zero, dim3((p.nb + 255) / 256), dim3(256), 0, s, cursor, (int64_t)p.nb);
   const int rows_wg = kRouteItems / (int)a.C;
-  const size_t lds_route = (size_t)kRouteItems * (4 + 2) + (size_t)2 * p.nb * 4 + (a.bag_off ? (size_t)rows_wg * 4 : 0);
+  const size_t lds_route = (size_t)kRouteItems * (4 + 2 + 2) + (size_t)3 * p.nb * 4 + (a.bag_off ? (size_t)rows_wg * 4 : 0);
   static std::atomic<bool> configured{false};   // per instantiation; a race between host threads only repeats the call
   if (!configured.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 2048) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) != hipSuccess)   // the kernel also has kRouteThreads * 4 bytes of static LDS
       return ROAST_ERR_HIP;
     configured.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL(k_embed_route<FIXED>, dim3((unsigned)((a.N + rows_wg - 1) / rows_wg)), dim3(256), lds_route, s, a,
+  hipLaunchKernelGGL(k_embed_route<FIXED>, dim3((unsigned)((a.N + rows_wg - 1) / rows_wg)), dim3(kRouteThreads), lds_route, s, a,
                      p.r_log2, p.nb, p.cap, walk_ok(a), rows, tables, cursor, list, dOut, dM, pbits, fs, acc);
   const int segs = (int)((p.cap + kSeg - 1) / kSeg);
   const size_t lds = ((size_t)(1 << p.r_log2) + a.Z) * 8;
