@@ -880,6 +880,12 @@ __global__ __launch_bounds__(256) void k_split_finish_f32(const float* __restric
 inline int64_t shadow_stride_of(int64_t m_size) { return (m_size + 1 + 63) / 64 * 64; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+// True when blocks of kBNarrow columns fill the 256 CUs in fewer or shorter rounds than blocks of
+// kBN columns do (rb row blocks, n output columns): 8192 x 768 outputs are 192 blocks of 128 columns
+// but exactly 256 of 96.
+inline bool narrow_pays(int64_t rb, int64_t n) {
+  return cdiv(rb * cdiv(n, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(n, kBN), 256) * kBN;
+}
 
 }  // namespace
 
@@ -977,9 +983,8 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   // the shadow is read in 8-column pieces, which must not straddle tiles
   const bool shadow = M_bf16 && a.Z2 % 8 == 0;
   roast_status st;
-  const int64_t rb = cdiv(a.I, BM);             // narrow blocks: see mfma_mm_bwd_dx
-  const bool narrow = shadow && a.H % BK == 0 && grid.z == 1 &&
-                      cdiv(rb * cdiv(a.O, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(a.O, BN), 256) * BN;
+  // a narrower block (256 x 96, eight 32 x 96 consumer tiles) when it fills the CUs better
+  const bool narrow = shadow && a.H % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.O);
   if (narrow) {
     grid.x = (unsigned)cdiv(a.O, kBNarrow);
     st = launch<MODE_FWD, BM, kBNarrow, 8, 1, true>(p, grid, s);
@@ -1002,11 +1007,7 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   split_setup(&p, &grid, a.O, mfma_dx_splits(a), ws);
   roast_status st;
-  // A narrower block (256 x 96, eight 32 x 96 consumer tiles) when it fills the 256 CUs in fewer or
-  // shorter rounds: 8192 x 768 outputs are 192 blocks of 128 columns but exactly 256 of 96.
-  const int64_t rb = cdiv(a.I, BM);
-  const bool narrow = M_bf16 && a.O % BK == 0 && grid.z == 1 &&
-                      cdiv(rb * cdiv(a.H, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(a.H, BN), 256) * BN;
+  const bool narrow = M_bf16 && a.O % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.H);
   if (narrow) {
     grid.x = (unsigned)cdiv(a.H, kBNarrow);
     st = launch<MODE_DX, BM, kBNarrow, 8, 1, true>(p, grid, s);
@@ -1110,8 +1111,12 @@ roast_status x3_mm_fwd(const MMArgs& a, const float* X, int64_t ldx, const float
   p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = Y; p.ldc = ldy;
   dim3 grid((unsigned)cdiv(a.O, kBN), (unsigned)cdiv(a.I, kBM), 1);
   split_setup(&p, &grid, a.H, x3_fwd_splits(a), parts);
-  st = a.H % BK != 0 ? launch<MODE_FWD, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
-                     : launch<MODE_FWD, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  if (grid.z == 1 && a.H % BK == 0 && narrow_pays(cdiv(a.I, kBM), a.O)) {
+    grid.x = (unsigned)cdiv(a.O, kBNarrow);
+    st = launch<MODE_FWD, kBM, kBNarrow, 8, 1, true, true>(p, grid, s);
+  } else
+    st = a.H % BK != 0 ? launch<MODE_FWD, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
+                       : launch<MODE_FWD, kBM, kBN, 4, 2, true, true>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
@@ -1132,8 +1137,12 @@ roast_status x3_mm_bwd_dx(const MMArgs& a, const float* dY, int64_t ldy, const f
   p.mb_stride = shadow_stride_of(a.m_size); p.mb_plane = 2 * p.mb_stride; p.C32 = dX; p.ldc = ldx;
   dim3 grid((unsigned)cdiv(a.H, kBN), (unsigned)cdiv(a.I, kBM), 1);
   split_setup(&p, &grid, a.O, x3_dx_splits(a), parts);
-  st = a.O % BK != 0 ? launch<MODE_DX, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
-                     : launch<MODE_DX, kBM, kBN, 4, 2, true, true>(p, grid, s);
+  if (grid.z == 1 && a.O % BK == 0 && narrow_pays(cdiv(a.I, kBM), a.H)) {
+    grid.x = (unsigned)cdiv(a.H, kBNarrow);
+    st = launch<MODE_DX, kBM, kBNarrow, 8, 1, true, true>(p, grid, s);
+  } else
+    st = a.O % BK != 0 ? launch<MODE_DX, kBM, kBN, 4, 2, true, true, true>(p, grid, s)
+                       : launch<MODE_DX, kBM, kBN, 4, 2, true, true>(p, grid, s);
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 
