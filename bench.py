@@ -60,6 +60,9 @@ def parse():
                    help="atomic mode only: give roast_mm_bwd_dM its optional scratch (contraction parts x H x O "
                         "floats per call); about 7 %% faster dM, but a buffer of the size of the virtual weights, "
                         "which the method otherwise never needs")
+    p.add_argument("--graph", action="store_true",
+                   help="--workload cfg*: capture one step in a HIP graph and time replays (what a launch-bound "
+                        "loop like config 1 gains from it)")
     p.add_argument("--calibration-copy", action="store_true",
                    help="profiling aid: also launch one plain 256 MiB device copy per step, the kernel of known "
                         "size that the FETCH_SIZE / WRITE_SIZE counters are scaled by")
@@ -149,12 +152,23 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
 
     for _ in range(args.warmup):
         step()
+    run = step
+    if args.graph:
+        # the library only launches kernels (no allocation, no synchronisation, no memset), so a step
+        # can be captured once its kernels have been configured by the warm-up calls above
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+        for _ in range(3):
+            run()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
     for _ in range(args.steps):
-        step()
+        run()
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -168,7 +182,7 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
             "data": "synthetic", "pct_mfma_peak": 100.0 * tflops / peak,
             "config": {"workload": f"{cfg.name}: I={cfg.I}, {len(cfg.layers)} layer call(s), {cfg.Z1}x{cfg.Z2} tiles, "
                                    f"|M|={cfg.m_size}, {cfg.dtype}", "reduce": args.reduce, "dm_workspace": ws is not None,
-                       "f32_on_matrix_cores": wf is not None},
+                       "f32_on_matrix_cores": wf is not None, "hip_graph": bool(args.graph)},
             "roofline": {"kernel": "whole step (all MM kernels)", "bound": "mfma" if bf16 else "alu", "achieved": tflops,
                          "peak": peak, "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None}}
 

@@ -25,6 +25,10 @@
  *   - Errors are return codes; nothing is launched when a call returns non-zero, except
  *     ROAST_ERR_HIP which reports a launch failure from the runtime.
  *   - Sizes of zero rows (I == 0, N == 0) are a successful no-op.
+ *   - A call only enqueues kernels on `stream`: no allocation, no synchronisation, no memset or
+ *     copy.  A sequence of calls may therefore be recorded in a HIP graph, once every kernel of the
+ *     sequence has run once outside the capture (a kernel's first launch in a process sets a
+ *     function attribute).
  *   - Every shape is accepted; which kernels run is a matter of speed, never of results beyond the
  *     stated tolerances.  The matrix-core kernels take ROAST_BF16 calls (and ROAST_F32 calls that
  *     come with a workspace, see roast_mm_fwd_ws) with 16-byte aligned pointers, leading dimensions
