@@ -65,6 +65,13 @@ def load() -> C.CDLL:
     if _lib is not None:
         return _lib
     path = os.environ.get("ROAST_HIP_LIB", LIB_PATH)     # override: point at another build of the same library
+    # PyTorch-ROCm ships its own HIP runtime.  If this library were loaded first it would bring in the
+    # system's copy, and the process would hold two runtimes: kernels launched through one on
+    # streams and pointers of the other fail.  Importing torch first makes its runtime the one both use.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if path == LIB_PATH and not os.path.exists(LIB_PATH):
         from . import build as _build
         _build.build()

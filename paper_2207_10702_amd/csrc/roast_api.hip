@@ -55,6 +55,11 @@ bool mode_ok(roast_reduce_mode m) { return m == ROAST_REDUCE_ATOMIC || m == ROAS
 
 }  // namespace
 
+// The runtime keeps the last error of ANY earlier HIP call of the process (the caller's own, or a
+// framework's probe that is expected to fail) until somebody reads it; an entry point that launches
+// kernels drops it first, so that the status it returns is about its own launches.
+static inline void drop_stale_error() { (void)hipGetLastError(); }
+
 extern "C" {
 
 const char* roast_status_string(roast_status s) {
@@ -83,6 +88,7 @@ roast_status roast_tile_index(const roast_mm_desc* d, int64_t* off_host, int8_t*
 }
 
 roast_status roast_tile_index_device(const roast_mm_desc* d, int64_t* off_dev, int8_t* sgn_dev, void* stream) {
+  drop_stale_error();
   MMArgs a;
   roast_status st = make_mm_args(d, 0, &a);
   if (st != ROAST_OK) return st;
@@ -92,6 +98,7 @@ roast_status roast_tile_index_device(const roast_mm_desc* d, int64_t* off_dev, i
 
 roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, const int64_t* rows,
                                       const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream) {
+  drop_stale_error();
   EmbedArgs a;
   roast_status st = make_embed_args(d, N, &a);
   if (st != ROAST_OK) return st;
@@ -107,6 +114,7 @@ size_t roast_m_shadow_bytes(int64_t m_size) {
 size_t roast_m_planes_bytes(int64_t m_size) { return m_size > 0 ? m_planes_bytes(m_size) : 0; }
 
 roast_status roast_m_planes_bf16(const float* M, int64_t m_size, void* planes, void* stream) {
+  drop_stale_error();
   if (m_size < 0) return ROAST_ERR_ARG;
   if (m_size == 0) return ROAST_OK;
   if (!M || !planes || ((uintptr_t)planes & 15) != 0) return ROAST_ERR_ARG;
@@ -114,6 +122,7 @@ roast_status roast_m_planes_bf16(const float* M, int64_t m_size, void* planes, v
 }
 
 roast_status roast_m_shadow_bf16(const float* M, int64_t m_size, void* shadow, void* stream) {
+  drop_stale_error();
   if (m_size < 0) return ROAST_ERR_ARG;
   if (m_size == 0) return ROAST_OK;
   if (!M || !shadow || ((uintptr_t)shadow & 15) != 0) return ROAST_ERR_ARG;
@@ -139,6 +148,7 @@ size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t
 roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
                              const float* M, const void* M_bf16, void* Y, int64_t ldy, void* workspace,
                              size_t workspace_bytes, void* stream) {
+  drop_stale_error();
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -169,6 +179,7 @@ roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, con
 roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
                                 const float* M, const void* M_bf16, void* dX, int64_t ldx, void* workspace,
                                 size_t workspace_bytes, void* stream) {
+  drop_stale_error();
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -212,6 +223,7 @@ size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce
 roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
                              const void* dY, int64_t ldy, float* dM, roast_reduce_mode mode, void* ws,
                              size_t ws_bytes, void* stream) {
+  drop_stale_error();
   MMArgs a;
   roast_status st = make_mm_args(d, I, &a);
   if (st != ROAST_OK) return st;
@@ -246,6 +258,7 @@ roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
 
 roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t* rows, const uint32_t* table_ids,
                              const float* M, float* out, void* stream) {
+  drop_stale_error();
   EmbedArgs a;
   roast_status st = make_embed_args(d, N, &a);
   if (st != ROAST_OK) return st;
@@ -264,6 +277,7 @@ size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_red
 roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t* rows, const uint32_t* table_ids,
                              const float* dOut, float* dM, roast_reduce_mode mode, void* ws, size_t ws_bytes,
                              void* stream) {
+  drop_stale_error();
   EmbedArgs a;
   roast_status st = make_embed_args(d, N, &a);
   if (st != ROAST_OK) return st;
@@ -282,6 +296,7 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
 roast_status roast_embed_bag_fwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
                                  const uint32_t* table_ids, const int64_t* bag_offsets, const float* M, float* out,
                                  void* stream) {
+  drop_stale_error();
   EmbedArgs a;
   roast_status st = make_embed_args(d, N, &a);
   if (st != ROAST_OK) return st;
@@ -303,6 +318,7 @@ size_t roast_embed_bag_bwd_workspace(const roast_embed_desc* d, int64_t N, int64
 roast_status roast_embed_bag_bwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
                                  const uint32_t* table_ids, const int64_t* bag_offsets, const float* dOut, float* dM,
                                  roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream) {
+  drop_stale_error();
   EmbedArgs a;
   roast_status st = make_embed_args(d, N, &a);
   if (st != ROAST_OK) return st;
@@ -322,6 +338,7 @@ roast_status roast_embed_bag_bwd(const roast_embed_desc* d, int64_t N, int64_t B
 
 roast_status roast_optim_step(const roast_optim_desc* d, int64_t m_size, float* M, float* dM, float* state1,
                               float* state2, void* M_bf16, void* stream) {
+  drop_stale_error();
   if (!d || m_size < 0) return ROAST_ERR_ARG;
   if (d->kind != ROAST_OPT_SGD && d->kind != ROAST_OPT_ADAGRAD && d->kind != ROAST_OPT_ADAM) return ROAST_ERR_ARG;
   if (d->kind == ROAST_OPT_ADAM &&
