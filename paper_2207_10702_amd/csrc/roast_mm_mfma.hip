@@ -707,7 +707,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;     // (only when CPR does not divide 64)
         const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + cc * 16);
         const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 8;
-        if (row < Mdim && col < Ndim) *reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col) = v;
+        if (row < Mdim && col < Ndim) __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col));
       }
     }
   } else {
