@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0
 # scaled by what the counter reads for a plain 256 MiB copy; profiles/bench_default_pmc_hbm_traffic.txt).
 # Valid for the default workload only.
 MEASURED_TRAFFIC_BYTES = {"mm_fwd_l1": 64.6e6, "mm_fwd_l2": 64.6e6, "mm_bwd_dx_l1": 64.6e6, "mm_bwd_dx_l2": 64.6e6,
-                          "embed_fwd": 1185.9e6}
+                          "embed_fwd": 964.6e6}
 
 
 def parse():
