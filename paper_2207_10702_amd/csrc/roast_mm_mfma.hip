@@ -682,7 +682,11 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;   // (only when CPR does not divide 64)
           const float4v v = *reinterpret_cast<const float4v*>(ebuf + r * ES + cc * 16);
           const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 4;
-          if (row < Mdim && col < Ndim) *reinterpret_cast<float4v*>(part + row * ldp + col) = v;
+          if (row < Mdim && col < Ndim) {
+            // partial tiles are read again by the finishing kernel; a final result is not
+            if (p.G) *reinterpret_cast<float4v*>(part + row * ldp + col) = v;
+            else __builtin_nontemporal_store(v, reinterpret_cast<float4v*>(part + row * ldp + col));
+          }
         }
       }
       return;
