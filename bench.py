@@ -26,11 +26,53 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 bf16 FLOP/clk/CU x 2.4 GHz, dense
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per launch (FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this script, each
-# scaled by what the counter reads for a plain 256 MiB copy; profiles/bench_default_pmc_hbm_traffic.txt).
-# Valid for the default workload only.
-MEASURED_TRAFFIC_BYTES = {"mm_fwd_l1": 64.6e6, "mm_fwd_l2": 64.6e6, "mm_bwd_dx_l1": 64.6e6, "mm_bwd_dx_l2": 64.6e6,
-                          "embed_fwd": 964.6e6}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "bench_default_pmc_hbm_traffic.txt")
+
+
+def load_measured_traffic(path=TRAFFIC_PROFILE):
+    """HBM-side bytes per call of the default workload, read from the committed rocprofv3 summary
+    (FETCH_SIZE + WRITE_SIZE of two --pmc runs of this script, each scaled by what the counter reads
+    for a plain 256 MiB copy).  The summary carries one line per call of the step:
+        traffic: <call> | <kernel(s) that serve it> | <fetched bytes> | <written bytes>
+    Returns {call: {"kernels": str, "fetch": bytes, "write": bytes}}.  A missing file or a malformed
+    line is an error: a roofline without its traffic figure would silently go stale."""
+    rows = {}
+    with open(path) as f:
+        for line in f:
+            if not line.startswith("traffic:"):
+                continue
+            parts = [x.strip() for x in line[len("traffic:"):].split("|")]
+            if len(parts) != 4 or not parts[1]:
+                raise ValueError(f"{path}: malformed traffic line: {line!r}")
+            rows[parts[0]] = {"kernels": parts[1], "fetch": float(parts[2]), "write": float(parts[3])}
+    if not rows:
+        raise ValueError(f"{path}: no 'traffic:' lines")
+    return rows
+
+
+def traffic_of(rows, calls, kernel_substr):
+    """Sum of fetched + written bytes over `calls`; every call must be in the summary and be served by a
+    kernel whose name contains `kernel_substr` (else the summary belongs to another build)."""
+    total = 0.0
+    for c in calls:
+        if c not in rows:
+            raise KeyError(f"{TRAFFIC_PROFILE}: no traffic line for call {c!r}")
+        if kernel_substr not in rows[c]["kernels"]:
+            raise KeyError(f"{TRAFFIC_PROFILE}: call {c!r} is listed with kernels {rows[c]['kernels']!r}, "
+                           f"expected {kernel_substr!r}")
+        total += rows[c]["fetch"] + rows[c]["write"]
+    return total
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def parse():
@@ -98,9 +140,11 @@ def time_optimizer(roast, torch, M, dM, Mb):
     return out
 
 
-def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
+def bench_mm_config(args, roast, wl, torch, np, to_dev, mode, workload=None, steps=None, warmup=None):
     """Forward, dX and dM of every layer of one ROAST-MM configuration, all layers sharing M and dM."""
-    cfg = wl.CONFIGS[args.workload]
+    cfg = wl.CONFIGS[workload or args.workload]
+    steps = args.steps if steps is None else steps
+    warmup = args.warmup if warmup is None else warmup
     if args.dtype == "f32":
         import dataclasses
         cfg = dataclasses.replace(cfg, dtype="f32")
@@ -150,7 +194,7 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
             roast.roast_mm_bwd_dx(d, dY, M, dX, M_bf16=Mb, ws=wx)
             roast.roast_mm_bwd_dM(d, X, dY, dM, mode, ws)
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     run = step
     if args.graph:
@@ -167,17 +211,17 @@ def bench_mm_config(args, roast, wl, torch, np, to_dev, mode):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     e0.record()
-    for _ in range(args.steps):
+    for _ in range(steps):
         run()
     e1.record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    ms = e0.elapsed_time(e1) / args.steps
+    ms = e0.elapsed_time(e1) / steps
     flop = 3.0 * sum(2.0 * cfg.I * l.H * l.O for l in cfg.layers)
     peak = PEAK_BF16_TFLOPS if bf16 else 157.3
     tflops = flop / (ms * 1e-3) / 1e12
     return {"metric": "ROAST-MM fwd+bwd TFLOP/s (% MFMA peak)", "unit": "TFLOP/s", "value": tflops, "n_gpus": 1,
-            "steps": args.steps, "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / args.steps, "mm_ms": ms,
+            "steps": steps, "warmup": warmup, "ms_per_step": (t1 - t0) * 1e3 / steps, "mm_ms": ms,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if bf16 else "f32",
             "data": "synthetic", "pct_mfma_peak": 100.0 * tflops / peak,
             "config": {"workload": f"{cfg.name}: I={cfg.I}, {len(cfg.layers)} layer call(s), {cfg.Z1}x{cfg.Z2} tiles, "
@@ -287,7 +331,7 @@ def main():
     import torch
 
     from paper_2207_10702_amd import binding as roast, workloads as wl
-    from tests.util import to_dev
+    from paper_2207_10702_amd.checks import to_dev
 
     roast.load()
     torch.cuda.set_device(0)
@@ -414,14 +458,28 @@ def main():
         result["value"] = tflops
         result["mm_ms"] = mm_ms
         result["pct_mfma_peak"] = 100.0 * tflops / PEAK_BF16_TFLOPS
-        # The dominant kernel of the MM path is the MFMA kernel template (forward, dX and the dM
-        # products are its three modes).  A forward / dX call is exactly one launch of it, so the
-        # call's event time is the kernel's duration; the slowest of those four launches is reported.
-        dom = max((k for k in per_call if k.startswith(("mm_fwd", "mm_bwd_dx"))), key=lambda k: per_call[k])
-        ach = flop_layer[dom[-2:]] / (per_call[dom] * 1e-3) / 1e12
-        result["roofline"] = {"kernel": "k_roast_mfma (" + dom + ")", "bound": "mfma", "achieved": ach,
-                              "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                              "traffic": MEASURED_TRAFFIC_BYTES.get(dom)}
+        # Per-call rooflines.  A forward / dX / dM call in this configuration (bf16 shadow, atomic dM
+        # without workspace) is exactly one launch of one instantiation of the MFMA kernel template,
+        # so the call's HIP-event time on the launch stream is that kernel's duration.
+        mm_calls = [k for k in per_call if k.startswith("mm_")]
+        result["roofline_per_call"] = {
+            k: {"achieved": flop_layer[k[-2:]] / (per_call[k] * 1e-3) / 1e12, "unit": "TFLOP/s",
+                "frac": flop_layer[k[-2:]] / (per_call[k] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS} for k in mm_calls}
+        # The dominant kernel = the instantiation with the largest total time per step: the dM
+        # product (MODE 2, two launches per step, one per layer; both 38.65 GFLOP).
+        by_kind = {"k_roast_mfma<MODE_DM> (mm_bwd_dM_l1 + mm_bwd_dM_l2)": ["mm_bwd_dM_l1", "mm_bwd_dM_l2"],
+                   "k_roast_mfma<MODE_FWD> (mm_fwd_l1 + mm_fwd_l2)": ["mm_fwd_l1", "mm_fwd_l2"],
+                   "k_roast_mfma<MODE_DX> (mm_bwd_dx_l1 + mm_bwd_dx_l2)": ["mm_bwd_dx_l1", "mm_bwd_dx_l2"]}
+        dom = max(by_kind, key=lambda k: sum(per_call[c] for c in by_kind[k]))
+        calls = by_kind[dom]
+        ach = sum(flop_layer[c[-2:]] for c in calls) / (sum(per_call[c] for c in calls) * 1e-3) / 1e12
+        traffic = None
+        if args.reduce == "atomic" and ws is None:       # the configuration the committed summary was taken in
+            traffic = traffic_of(load_measured_traffic(), calls, "k_roast_mfma") / len(calls)
+        result["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
+                              "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
+                              "launches_per_step": len(calls),
+                              "avg_launch_us": 1e3 * sum(per_call[c] for c in calls) / len(calls)}
     if not args.mm_only:
         # compulsory HBM bytes: output (or dOut) once, ids once, M (and dM read+write) once
         ids = N * (8 + 4)
@@ -430,11 +488,19 @@ def main():
         gbs_f = bytes_fwd / (per_call["embed_fwd"] * 1e-3) / 1e9
         gbs_b = bytes_bwd / (per_call["embed_bwd"] * 1e-3) / 1e9
         tot = (bytes_fwd + bytes_bwd) / ((per_call["embed_fwd"] + per_call["embed_bwd"]) * 1e-3) / 1e9
+        tr = load_measured_traffic() if args.reduce == "atomic" else None
         result["embedding"] = {"value": tot, "unit": "GB/s", "pct_hbm_peak": 100.0 * tot / PEAK_HBM_GBS,
                                "fwd_GBs": gbs_f, "bwd_GBs": gbs_b, "bytes_fwd": bytes_fwd, "bytes_bwd": bytes_bwd,
-                               "roofline": {"kernel": "k_embed (embed_fwd)", "bound": "hbm", "achieved": gbs_f,
-                                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
-                                            "traffic": MEASURED_TRAFFIC_BYTES.get("embed_fwd")}}
+                               # the gradient is the larger consumer of the two (and of the whole step):
+                               # its kernels together (zero + route + accumulate = one call) are the
+                               # dominant HBM-bound work
+                               "roofline": {"kernel": "k_embed_zero + k_embed_route + k_embed_accum (embed_bwd)",
+                                            "bound": "hbm", "achieved": gbs_b, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                            "frac": gbs_b / PEAK_HBM_GBS,
+                                            "traffic": traffic_of(tr, ["embed_bwd"], "k_embed_accum") if tr else None},
+                               "roofline_fwd": {"kernel": "k_embed (embed_fwd)", "bound": "hbm", "achieved": gbs_f,
+                                                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs_f / PEAK_HBM_GBS,
+                                                "traffic": traffic_of(tr, ["embed_fwd"], "k_embed") if tr else None}}
         if not args.hot_path_only:
             # the pooled reading of "gather-sum": one output row per sample = the sum of its 26 lookups
             nb = N // ecfg.n_tables
@@ -468,6 +534,21 @@ def main():
             result["dtype"] = "f32"
             result["roofline"] = result["embedding"]["roofline"]
 
+    # The other ROAST-MM configurations (outside `value`): forward, dX and dM of every layer, timed
+    # as a whole step each, with their fraction of the MFMA peak (fp32 for config 1: it runs on the
+    # bf16 matrix cores from bfloat16 planes and is priced against the fp32 MFMA peak).
+    if not args.embed_only and not args.hot_path_only and not args.mm_only and args.reduce == "atomic" and ws is None:
+        del X, dY, H1, Y, dH1, dX, out, dOut, rows, tables
+        torch.cuda.empty_cache()
+        others = {}
+        for name, st, wu in (("cfg1_single_f32", 50, 10), ("cfg3_bert_stack_bf16", 8, 2), ("cfg5_large_bf16", 8, 2)):
+            r = bench_mm_config(args, roast, wl, torch, np, to_dev, mode, workload=name, steps=st, warmup=wu)
+            others[name] = {"workload": r["config"]["workload"], "ms_per_step": r["mm_ms"], "TFLOPs": r["value"],
+                            "dtype": r["dtype"], "peak_TFLOPs": r["roofline"]["peak"], "frac": r["roofline"]["frac"],
+                            "steps": st, "warmup": wu}
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
+
     if not args.no_cpu_baseline and not args.embed_only:
         import oracle
         # bounded sample: the first `rows_s` tokens through forward, dX and dW (+ scatter) of both layers
@@ -488,9 +569,10 @@ def main():
         flop_s = 3.0 * (flop_layer["l1"] + flop_layer["l2"]) * rows_s / I
         result["cpu_baseline"] = {"value": flop_s / (c1 - c0) / 1e12, "unit": "TFLOP/s",
                                   "cores": oracle.num_threads(), "kind": "oracle",
+                                  "cpu_model": cpu_model(), "host_logical_cpus": os.cpu_count(),
                                   "sample": f"{rows_s} of {I} tokens of cfg2 through fwd, dX and dM of both layers "
                                             f"(W materialised element by element, fp64 triple loops, OpenMP over "
-                                            f"rows), {c1 - c0:.1f} s wall"}
+                                            f"rows, {oracle.num_threads()} threads), {c1 - c0:.1f} s wall"}
     print(json.dumps(result))
 
 

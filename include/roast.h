@@ -4,9 +4,9 @@
  * ROAST (arXiv 2207.10702) keeps every learnable parameter of a model in one small flat array M
  * and recovers weights from it block by block: a ROAST-MM layer's virtual weight matrix W (H x O)
  * is cut into Z1 x Z2 tiles, tile (x, y) is the contiguous, row-major slice of M that starts at a
- * hashed offset, times a hashed +-1 sign and a per-module scale lambda (Section 3.1, "Matrix
+ * hashed offset, times a hashed +-1 sign and a per-module scale lambda (Section 4.1, "Matrix
  * multiplication" paragraph and Algorithm 1); an embedding row is recovered the same way in 1-D
- * chunks of Z scalars (Section 3.1, "Lookup" paragraph).  W is never materialised.
+ * chunks of Z scalars (Section 4.1, "Lookup" paragraph).  W is never materialised.
  *
  * Conventions shared by every entry point
  *   - Pointers named X, Y, dY, dX, M, dM, out, dOut, rows, table_ids, ws are DEVICE pointers owned
@@ -20,17 +20,25 @@
  *     bfloat16 (nearest even) when it is staged as the MFMA weight operand and lambda is applied to
  *     the fp32 accumulator.
  *   - dM is ACCUMULATED INTO (dM += ...): all layers sharing one M add into one gradient buffer
- *     (global memory sharing, Section 3.2; gradient equation of Section 3.3).  The caller zeroes it.
+ *     (global memory sharing, Section 4.2; gradient equation of Section 4.3).  The caller zeroes it.
  *   - M is never written.  No entry point touches memory outside the extents stated below.
  *   - Errors are return codes; nothing is launched when a call returns non-zero, except
  *     ROAST_ERR_HIP which reports a launch failure from the runtime.
+ *   - The HIP runtime keeps one "last error" per host thread, whoever caused it.  Every entry point
+ *     that launches kernels reads -- and thereby CLEARS -- that value before it launches, so that
+ *     ROAST_ERR_HIP is about this library's own launches only.  A caller that wants to see an
+ *     error left behind by its own earlier HIP calls must read hipGetLastError() before it calls
+ *     into this library; afterwards it is gone.
  *   - Sizes of zero rows (I == 0, N == 0) are a successful no-op.
  *   - A call only enqueues kernels on `stream`: no allocation, no synchronisation, no memset or
  *     copy.  A sequence of calls may therefore be recorded in a HIP graph, once every kernel of the
  *     sequence has run once outside the capture (a kernel's first launch in a process sets a
  *     function attribute).
- *   - Every shape is accepted; which kernels run is a matter of speed, never of results beyond the
- *     stated tolerances.  The matrix-core kernels take ROAST_BF16 calls (and ROAST_F32 calls that
+ *   - Every shape within the limits below is accepted; which kernels run is a matter of speed,
+ *     never of results beyond the stated tolerances.  Limits (ROAST_ERR_UNSUPPORTED beyond them):
+ *     H, O, I, D < 2^31; the generic ROAST-MM kernels (any call the matrix-core kernels do not
+ *     take) handle at most 65535 * 64 = 4 194 240 rows I; DETERMINISTIC roast_mm_bwd_dM at most
+ *     2^17 = 131 072 tiles per layer; DETERMINISTIC lookup gradients fewer than 2^40 chunks.  The matrix-core kernels take ROAST_BF16 calls (and ROAST_F32 calls that
  *     come with a workspace, see roast_mm_fwd_ws) with 16-byte aligned pointers, leading dimensions
  *     that are multiples of 8, H and O multiples of 8, and tiles with Z1 % 8 == 0 and Z2 % 4 == 0
  *     (forward), Z2 % 8 == 0 (dX), Z1 % 4 == 0 (dM), per-block sign; the lookup kernels are fastest
@@ -65,8 +73,8 @@ typedef enum { ROAST_F32 = 0, ROAST_BF16 = 1 } roast_dtype;
 typedef enum { ROAST_REDUCE_ATOMIC = 0, ROAST_REDUCE_DETERMINISTIC = 1 } roast_reduce_mode;
 
 /*
- * Hash parameters.  The paper asks only for "a universal hash function" h1 / h2 with range
- * {0, ..., |M| - block} and an independent sign hash g (Section 3.1); this library uses the
+ * Hash parameters.  The paper asks only for universal hash functions h1 / h2 with range
+ * {0, ..., |M| - block} and an independent sign hash g (Section 4.1); this library uses the
  * Carter-Wegman multiply-add family over a prime P on the 3-part key (k0, k1, k2):
  *
  *     u      = ((a0*(k0 mod P)) mod P + (a1*(k1 mod P)) mod P + (a2*(k2 mod P)) mod P + a3) mod P
@@ -78,12 +86,12 @@ typedef enum { ROAST_REDUCE_ATOMIC = 0, ROAST_REDUCE_DETERMINISTIC = 1 } roast_r
  * like the offset -- the reading this library takes as the default, and the one its fast kernels
  * implement.  use_sign = 2: one sign per element, v keyed by the element's own coordinates
  * ((layer_id, i, j) for W[i,j]; (table_id, row, d) for element d of a looked-up row), the form the
- * analysis of Section 3.4 uses; this variant runs on the generic kernels.  Other values:
+ * analysis of Section 5 uses; this variant runs on the generic kernels.  Other values:
  * ROAST_ERR_RANGE.
  *
  * ROAST-MM keys: (layer_id, x, y) with x the tile row (along H) and y the tile column (along O),
- * block = Z1*Z2.  Lookup keys: (table_id, row, chunk), block = Z.  "Each module uses independent
- * hash functions" (Section 3.1) is obtained by giving each module its own k0.
+ * block = Z1*Z2.  Lookup keys: (table_id, row, chunk), block = Z.  Modules get independent hash
+ * functions (Section 4.1 asks for that) by giving each module its own k0.
  * Requirements: 2 <= P < 2^32, every coefficient < P, align >= 1; otherwise ROAST_ERR_RANGE.
  */
 typedef struct {
@@ -123,7 +131,7 @@ typedef struct {
 const char* roast_status_string(roast_status s);
 
 /*
- * Tile -> (offset, sign) map of one layer: the hash h2 and sign g of Section 3.1 evaluated on the
+ * Tile -> (offset, sign) map of one layer: the hash h2 and sign g of Section 4.1 evaluated on the
  * whole ceil(H/Z1) x ceil(O/Z2) grid, on the HOST with the same integer code the kernels use.
  * off_host / sgn_host: HOST arrays of ntx*nty entries, row-major in (x, y); either may be NULL.
  */
@@ -134,7 +142,7 @@ roast_status roast_tile_index(const roast_mm_desc* d, int64_t* off_host, int8_t*
 roast_status roast_tile_index_device(const roast_mm_desc* d, int64_t* off_dev, int8_t* sgn_dev, void* stream);
 
 /* Chunk -> (offset, sign) of N lookups on the device: off_dev / sgn_dev hold N*ceil(D/Z) entries,
- * entry n*ceil(D/Z) + c for chunk c of lookup n (the hash h1 of Section 3.1). */
+ * entry n*ceil(D/Z) + c for chunk c of lookup n (the hash h1 of Section 4.1). */
 roast_status roast_chunk_index_device(const roast_embed_desc* d, int64_t N, const int64_t* rows,
                                       const uint32_t* table_ids, int64_t* off_dev, int8_t* sgn_dev, void* stream);
 
@@ -159,7 +167,7 @@ roast_status roast_mm_fwd(const roast_mm_desc* d, roast_dtype dt, int64_t I, con
                           const float* M, const void* M_bf16, void* Y, int64_t ldy, void* stream);
 
 /*
- * Gradient w.r.t. the input (Section 3.3):  dX[I x H] = dY[I x O] * W^T, W recovered from M.
+ * Gradient w.r.t. the input (Section 4.3):  dX[I x H] = dY[I x O] * W^T, W recovered from M.
  * dX is overwritten.  M_bf16 as for roast_mm_fwd.
  */
 roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* dY, int64_t ldy,
@@ -167,14 +175,16 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
 
 /*
  * Workspace variants of the two products above.  What the workspace buys depends on `dt`:
- *  - bf16, small batch (Section 3.2's blocked product; the paper's square-weight timings use batch
+ *  - bf16, small batch (Algorithm 1's blocked product; the square-weight timings of Section 6 use batch
  *    512): with few rows the output has too few tiles to fill the chip, so the contraction axis is
  *    split over workgroups; each writes an fp32 partial output to the workspace and a second pass
  *    sums the parts in a fixed order and rounds once to bf16.
  *  - fp32: the product runs on the bf16 matrix cores.  X (or dY) and M are each held in the
  *    workspace as three bfloat16 planes with x = hi + mid + lo exactly, and the six plane products of
- *    weight >= 2^-16 are accumulated in fp32; what is dropped is below 2^-23 of |x||w| per term,
- *    inside the fp32 bar of the conventions above.  Without a workspace fp32 runs on the vector ALUs.
+ *    weight >= 2^-16 are accumulated in fp32; the three dropped products -- (mid,lo), (lo,mid),
+ *    (lo,lo) -- are bounded by 2^-21 |x||w| per term in the worst case (planes are truncated, so
+ *    |mid| < 2^-7 |x| and |lo| < 2^-14 |x|) and are about 2^-24 |x||w| for typical mantissas: inside
+ *    the fp32 bar of the conventions above.  Without a workspace fp32 runs on the vector ALUs.
  * The *_workspace queries return the bytes that help for these sizes (0: nothing to gain, or a
  * shape the matrix-core kernels do not cover; the plain call is used).
  * workspace: NULL (same as the plain call), or a DEVICE buffer, 16-byte aligned, of at least the
@@ -185,6 +195,11 @@ roast_status roast_mm_bwd_dx(const roast_mm_desc* d, roast_dtype dt, int64_t I, 
  * fp32 calls only: the three bfloat16 planes of M (each in the layout of the bf16 shadow), made once
  * per update of M and passed as `M_bf16` to fp32 roast_mm_fwd_ws / roast_mm_bwd_dx_ws calls, which
  * otherwise rebuild them in their workspace on every call (a pass over |M|).
+ * NOTE: the `M_bf16` argument therefore names a different buffer per dtype -- ROAST_BF16 calls take
+ * the shadow (roast_m_shadow_bytes), ROAST_F32 calls with a workspace take the planes
+ * (roast_m_planes_bytes, three times as large).  The C-ABI carries no size for it and cannot tell
+ * them apart: passing a shadow to an fp32 call makes the kernels read past its end.  NULL is always
+ * safe.
  * planes: DEVICE buffer of roast_m_planes_bytes(m_size) bytes, 16-byte aligned, owned by the caller.
  */
 size_t roast_m_planes_bytes(int64_t m_size);
@@ -209,7 +224,7 @@ size_t roast_mm_bwd_dM_workspace(const roast_mm_desc* d, int64_t I, roast_reduce
 size_t roast_mm_bwd_dM_workspace_f32(const roast_mm_desc* d, int64_t I);
 
 /*
- * Gradient w.r.t. the shared array (Section 3.3 gradient equation, Appendix A.1):
+ * Gradient w.r.t. the shared array (Section 4.3 gradient equation, Appendix A.1):
  *   dM[offset(x,y) + Z2*o1 + o2] += lambda * sign(x,y) * sum_i X[i, x*Z1+o1] * dY[i, y*Z2+o2]
  * for every element of every tile; colliding tiles add up.  dM: m_size fp32, accumulated into.
  * ws / ws_bytes: device scratch of at least roast_mm_bwd_dM_workspace() bytes (may be NULL / 0
@@ -220,7 +235,7 @@ roast_status roast_mm_bwd_dM(const roast_mm_desc* d, roast_dtype dt, int64_t I,
                              float* dM, roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Lookup L(l, W) of Section 3.1 for N ids at once: out[N x D] fp32 (dense, row stride D),
+ * Lookup L(l, W) of Section 4.1 for N ids at once: out[N x D] fp32 (dense, row stride D),
  * rows: N int64 row ids (>= 0), table_ids: N uint32 (first hash key of each lookup).
  */
 roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t* rows,
@@ -233,7 +248,7 @@ roast_status roast_embed_fwd(const roast_embed_desc* d, int64_t N, const int64_t
 size_t roast_embed_bwd_workspace(const roast_embed_desc* d, int64_t N, roast_reduce_mode mode);
 
 /*
- * Gradient of the lookup (Section 3.3):  dM[offset(t,r,c) + o] += lambda * sign * dOut[n, c*Z + o].
+ * Gradient of the lookup (Section 4.3):  dM[offset(t,r,c) + o] += lambda * sign * dOut[n, c*Z + o].
  * dOut: N x D fp32 (row stride D); dM: m_size fp32, accumulated into.
  * DETERMINISTIC: every product fl(lambda * sign * dOut[..]) is converted to 64-bit fixed point with a
  * quantum derived from the largest |dOut| of the call (at least 31 bits below it), summed with
@@ -247,7 +262,7 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
                              roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Pooled (bag-sum) lookup: the lookup L of Section 3.1 applied to every id of a bag, summed per bag
+ * Pooled (bag-sum) lookup: the lookup L of Section 4.1 applied to every id of a bag, summed per bag
  * (the multi-hot use of an embedding table):
  *   out[b, :] = sum over n in [bag_offsets[b], bag_offsets[b+1]) of the row roast_embed_fwd returns
  *               for (rows[n], table_ids[n]);   out: B x D fp32 (row stride D), overwritten.
@@ -264,7 +279,7 @@ roast_status roast_embed_bag_fwd(const roast_embed_desc* d, int64_t N, int64_t B
 size_t roast_embed_bag_bwd_workspace(const roast_embed_desc* d, int64_t N, int64_t B, roast_reduce_mode mode);
 
 /*
- * Gradient of the pooled lookup (Section 3.3 applied to a sum: every lookup of bag b receives
+ * Gradient of the pooled lookup (Section 4.3 applied to a sum: every lookup of bag b receives
  * dOut[b, :]):  dM[offset(t,r,c) + o] += lambda * sign * dOut[bag(n), c*Z + o]  for all n.
  * dOut: B x D fp32 (row stride D); dM, mode, ws / ws_bytes as for roast_embed_bwd.
  */

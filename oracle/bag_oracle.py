@@ -1,13 +1,13 @@
 """CPU oracle for the pooled (bag-sum) ROAST lookup -- TEST INFRASTRUCTURE ONLY.
 
-The lookup operation L of Section 3.1 of arXiv 2207.10702 recovers one row per id; a pooled lookup
+The lookup operation L of Section 4.1 of arXiv 2207.10702 recovers one row per id; a pooled lookup
 returns, per bag, the sum of the rows of the bag's ids (the multi-hot / "gather-sum" use of an
 embedding table).  Nothing new is hashed: both functions are the plain definition on top of the
 per-lookup oracle, in float64, with no blocking or reordering.
 
   forward : out[b, :] = sum over n in [bag_offsets[b], bag_offsets[b+1]) of L(rows[n], tables[n])
   backward: the gradient of a sum hands every term the gradient of the sum, so lookup n of bag b
-            scatters dOut[b, :] exactly as the per-lookup gradient of Section 3.3 would scatter its
+            scatters dOut[b, :] exactly as the per-lookup gradient of Section 4.3 would scatter its
             own row.
 
 bag_offsets has B + 1 entries, starts at 0, is non-decreasing and ends at N (an empty bag yields a

@@ -9,24 +9,24 @@
  * library.  Everything floating point is done in double.
  *
  * What each function follows (arXiv 2207.10702):
- *   - oracle_locate           : the hash maps h1 / h2 (Section 3.1, "Lookup"
+ *   - oracle_locate           : the hash maps h1 / h2 (Section 4.1, "Lookup"
  *                               and "Matrix multiplication" paragraphs) and
- *                               the sign map g (end of Section 3.1).  The
- *                               paper only asks for "a universal hash
- *                               function"; the family used here is the
+ *                               the sign map g (end of Section 4.1).  The
+ *                               paper only asks for a universal hash
+ *                               function; the family used here is the
  *                               Carter-Wegman multiply-add-mod-prime family,
  *                               ((c0*k0 + c1*k1 + c2*k2 + c3) mod P) mod range.
  *   - oracle_elem_sign        : the per-element reading of the sign map g
- *                               (use_sign == 2; the theory of Section 3.4
+ *                               (use_sign == 2; the theory of Section 5
  *                               writes g(i) per parameter), same hash family,
  *                               keyed by the element's coordinates.
- *   - oracle_element_index    : the ROAST-MM mapping equation of Section 3.1,
+ *   - oracle_element_index    : the ROAST-MM mapping equation of Section 4.1,
  *                               W[i,j] = lambda * M[h2(C1,C2) + Z2*O1 + O2].
  *   - oracle_materialize_w    : that equation, evaluated element by element.
  *   - oracle_gemm_nn          : the result Algorithm 1 ensures, Y = X * W.
  *   - oracle_gemm_nt / _tn    : dX = dY * W^T and dW = X^T * dY, the ordinary
- *                               matrix-product gradients (Section 3.3).
- *   - oracle_scatter_dm       : the gradient equation of Section 3.3 /
+ *                               matrix-product gradients (Section 4.3).
+ *   - oracle_scatter_dm       : the gradient equation of Section 4.3 /
  *                               Appendix A.1: grad M[i] is the lambda-scaled
  *                               sum of the gradients of every recovered
  *                               parameter that maps to slot i (the sign g is
@@ -34,9 +34,9 @@
  *   - oracle_dm_window        : the same sum restricted to a window of slots,
  *                               so that big problems can be checked slot by
  *                               slot without forming all of dW.
- *   - oracle_embed_fwd / _bwd : the lookup equation of Section 3.1,
+ *   - oracle_embed_fwd / _bwd : the lookup equation of Section 4.1,
  *                               w[i] = lambda * M[h1(C(i)) + O(i)], and its
- *                               gradient by the same Section 3.3 sum.
+ *                               gradient by the same Section 4.3 sum.
  *
  * Parity pins for every function above are in tests/test_oracle_pins.py
  * (closed forms, library GEMM on the identity-hash special case, finite
@@ -48,6 +48,22 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* Threads the OpenMP loops below really get (reported next to the oracle's timing; no arithmetic). */
+int oracle_num_threads(void) {
+  int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+  {
+#pragma omp single
+    n = omp_get_num_threads();
+  }
+#endif
+  return n;
+}
 
 typedef struct {
   uint64_t P;              /* prime modulus, 2 <= P < 2^32                      */

@@ -40,6 +40,8 @@ def _load():
         HP = C.POINTER(OracleHash)
         i64, i32, u32, u64, dbl = C.c_int64, C.c_int32, C.c_uint32, C.c_uint64, C.c_double
         vp = C.c_void_p
+        lib.oracle_num_threads.argtypes = []
+        lib.oracle_num_threads.restype = C.c_int
         lib.oracle_locate.argtypes = [HP, u64, u64, u64, i64, i64, C.POINTER(i64), C.POINTER(i32)]
         lib.oracle_tile_index.argtypes = [HP, u32, i64, i64, i32, i32, i64, vp, vp]
         lib.oracle_element_index.argtypes = [HP, u32, i32, i32, i64, i64, i64, C.POINTER(i64), C.POINTER(i32)]
@@ -71,9 +73,8 @@ def _check(rc, what):
 
 
 def num_threads() -> int:
-    """Threads the OpenMP loops of the oracle will use."""
-    n = os.environ.get("OMP_NUM_THREADS")
-    return int(n) if n else (os.cpu_count() or 1)
+    """Threads the OpenMP loops of the oracle really get (asked of the OpenMP runtime itself)."""
+    return int(_load().oracle_num_threads())
 
 
 def locate(h, k0, k1, k2, m_size, length):

@@ -1,5 +1,5 @@
 // ROAST lookup kernels: out[n, c*Z + o] = lambda * sign * M[offset(table, row, c) + o]
-// (lookup equation of Section 3.1 of arXiv 2207.10702) and its scatter-add gradient (Section 3.3).
+// (lookup equation of Section 4.1 of arXiv 2207.10702) and its scatter-add gradient (Section 4.3).
 //
 // HBM-bound streaming kernels.  Work item = one chunk of one lookup, numbered g = n*C + c, so that
 // consecutive items are consecutive in `out`.  The integer work is done per lookup, not per chunk:
@@ -355,7 +355,7 @@ roast_status launch_embed(const EmbedArgs& a, const int64_t* rows, const uint32_
 // kMaxR slots; other shapes use the direct atomic kernel above.
 constexpr int kSeg = 8192;          // chunks per accumulate workgroup
 constexpr int kMaxBuckets = 2048;
-constexpr int kMaxR = 8192;         // largest bucket (slots), its fp64 LDS image is 64 KiB
+constexpr int kMaxR = 8192;         // largest bucket (slots); its fp64 LDS image is (kMaxR + Z) * 8 bytes, up to 72 KiB
 constexpr int kRouteItems = 4096;   // chunks per route workgroup (lookups per workgroup = kRouteItems / C)
 constexpr int kRouteThreads = 256;
 
@@ -714,6 +714,11 @@ roast_status bucket_run(const EmbedArgs& a, const BucketPlan& p, const int64_t* 
   if (!configured.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_route<FIXED>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 8192) != hipSuccess)   // the kernel also has kRouteThreads * 4 bytes of static LDS
+      return ROAST_ERR_HIP;
+    // the accumulate kernel's image passes 64 KiB once buckets have 8192 slots (|M| > 8 Mi): raise
+    // its limit here, before anything is launched, so that a refusal leaves dM untouched
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_embed_accum<FIXED>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (kMaxR + 1024) * 8) != hipSuccess)
       return ROAST_ERR_HIP;
     configured.store(true, std::memory_order_release);
   }

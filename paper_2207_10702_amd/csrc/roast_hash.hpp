@@ -1,7 +1,7 @@
 // Integer side of ROAST: block key -> (offset in M, sign).  Host and device share this one
 // implementation inside the library (the CPU oracle has its own, in plain C with % operators).
 //
-// The map is the Carter-Wegman family stated in roast.h (hash h1 / h2 and sign g of Section 3.1 of
+// The map is the Carter-Wegman family stated in roast.h (hash h1 / h2 and sign g of Section 4.1 of
 // arXiv 2207.10702).  Every `mod` is a Barrett reduction with a reciprocal prepared once on the
 // host, so the device never runs a 64-bit divide.
 #pragma once

@@ -1,7 +1,7 @@
 // Generic ROAST-MM kernels: any H, O, I, any tile size (down to 1x1), fp32 or bf16 activations.
 // They are the fp32 path and the fallback for shapes the MFMA kernels do not take.  Plain fp32 FMA
 // on a 64x64 output tile per workgroup, both operands staged through LDS; the weight operand is
-// read from M element by element through the tile hash (Section 3.1 mapping equation of
+// read from M element by element through the tile hash (Section 4.1 mapping equation of
 // arXiv 2207.10702), with a one-entry per-thread cache of the last tile's offset and sign.
 #include "roast_internal.hpp"
 

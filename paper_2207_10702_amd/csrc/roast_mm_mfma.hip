@@ -1,4 +1,4 @@
-// bf16 MFMA kernels for ROAST-MM on gfx950 (Algorithm 1 and the Section 3.3 gradients of
+// bf16 MFMA kernels for ROAST-MM on gfx950 (Algorithm 1 and the Section 4.3 gradients of
 // arXiv 2207.10702): forward Y = X*W, dX = dY*W^T and the per-tile products of dM = scatter(X^T*dY),
 // with W recovered from M tile by tile and never written to memory.
 //
@@ -8,8 +8,8 @@
 // bring the next operands into LDS.  Forward / dX run sixteen waves, 128 registers per lane: eight
 // consumers (two per SIMD, 64 x 64 each, so that one wave's LDS waits hide behind the other's
 // MFMAs), four producers that only issue the direct-to-LDS loads of the activation operand and
-// four that only stage the weight operand.  dM runs four consumers (128 x 64 each) and four
-// producers that stage both operands, because transposing both needs more registers.  The
+// four that only stage the weight operand.  dM runs the same sixteen waves: eight consumers and
+// eight producers, four transposing X and four transposing dY through registers.  The
 // contraction runs in steps of BK = 64 with one workgroup barrier per step.
 //
 // Both operands sit in LDS as [row][k] with 128-byte rows whose 16-byte chunks are XOR-swizzled,
@@ -204,8 +204,9 @@ struct RegSet {
 // X3: fp32 in, fp32 out on the bf16 matrix cores.  Every fp32 operand value x is held as three
 // bfloat16 planes with x = hi + mid + lo exactly (3 x 8 significand bits); a product x*w is the sum
 // of nine plane products, of which the six of weight >= 2^-16 are kept: (hi,hi) (hi,mid) (mid,hi)
-// (hi,lo) (lo,hi) (mid,mid).  What is dropped is below 2^-23 of |x||w|, the accumulation is the
-// usual fp32 one.  The contraction loop simply runs six times as many steps: step = 6*kq + pair.
+// (hi,lo) (lo,hi) (mid,mid).  The planes are truncated (|mid| < 2^-7 |x|, |lo| < 2^-14 |x|), so the
+// three dropped products are bounded by 2^-21 |x||w| per term in the worst case (mid and lo planes
+// all ones) and are near 2^-24 |x||w| for typical mantissas; the accumulation is the usual fp32 one.  The contraction loop simply runs six times as many steps: step = 6*kq + pair.
 // RAGK: the contraction length of forward / dX is a multiple of 8 but not of 64 (a separate
 // instantiation: the extra selects in the load waves cost the regular kernels 15 %).
 template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false>

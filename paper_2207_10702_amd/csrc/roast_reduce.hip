@@ -1,4 +1,4 @@
-// Deterministic reduction of the ROAST-MM gradient into M (gradient equation of Section 3.3 of
+// Deterministic reduction of the ROAST-MM gradient into M (gradient equation of Section 4.3 of
 // arXiv 2207.10702: every slot of M receives the lambda-scaled sum of the gradients of all
 // virtual weights hashed to it).
 //

@@ -2,9 +2,9 @@
 generators: no value here comes from the HIP library.  The paper prints no worked numeric example of
 its maps (its Figure 1 is a drawing), so these files are not the paper's numbers; they freeze what the
 oracle -- pinned elsewhere against unbounded-integer arithmetic, closed forms and library routines --
-computes for the mapping of Section 3.1 ("Matrix multiplication": tile (x, y) of layer l starts at
+computes for the mapping of Section 4.1 ("Matrix multiplication": tile (x, y) of layer l starts at
 h2(l, x, y); "Lookup": chunk c of row r of table t starts at h1(t, r, c); the sign g is described at
-the end of Section 3.1), so that a later change to the oracle's arithmetic cannot go unnoticed.
+the end of Section 4.1), so that a later change to the oracle's arithmetic cannot go unnoticed.
 
 Run from the repository root:  python tests/golden/make_golden.py
 """
@@ -33,7 +33,7 @@ def tile_file(name):
     off, sgn = oracle.tile_index(h, layer.layer_id, layer.H, layer.O, cfg.Z1, cfg.Z2, cfg.m_size)
     nty = -(-layer.O // cfg.Z2)
     with open(os.path.join(HERE, f"{name}_tile_index.txt"), "w") as f:
-        f.write("# tile map of Section 3.1 (offset h2(l,x,y) in {0..|M|-Z1*Z2}, sign g(l,x,y)), from oracle.tile_index\n")
+        f.write("# tile map of Section 4.1 (offset h2(l,x,y) in {0..|M|-Z1*Z2}, sign g(l,x,y)), from oracle.tile_index\n")
         f.write(f"# config {name}: H={layer.H} O={layer.O} Z1={cfg.Z1} Z2={cfg.Z2} |M|={cfg.m_size} layer={layer.layer_id}\n")
         f.write(f"# hash {hash_line(h)}\n# x y offset sign\n")
         for e in range(off.size):
@@ -51,7 +51,7 @@ def chunk_file():
     M = np.arange(1, m + 1, dtype=np.float32)
     out = oracle.embed_fwd(h, D, Z, 1.0, rows, tables, M)
     with open(os.path.join(HERE, "lookup_chunk_index.txt"), "w") as f:
-        f.write("# chunk map of Section 3.1 (\"Lookup\"): offset h1(t,r,c) in {0..|M|-Z} and sign, read off oracle.embed_fwd\n")
+        f.write("# chunk map of Section 4.1 (\"Lookup\"): offset h1(t,r,c) in {0..|M|-Z} and sign, read off oracle.embed_fwd\n")
         f.write(f"# D={D} Z={Z} |M|={m} lambda=1, M[i] = i + 1\n# hash {hash_line(h)}\n# table row chunk offset sign\n")
         for n in range(rows.size):
             for c in range(D // Z):

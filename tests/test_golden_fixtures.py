@@ -1,6 +1,6 @@
 """The stored index maps under tests/golden/ (written by tests/golden/make_golden.py from the oracle
 alone) against three independent evaluations: unbounded-integer arithmetic written out here from
-the mapping of Section 3.1, the oracle as it stands today, and the HIP library (host map on the CPU,
+the mapping of Section 4.1, the oracle as it stands today, and the HIP library (host map on the CPU,
 device maps and the lookup itself on the GPU)."""
 import os
 

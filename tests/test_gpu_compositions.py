@@ -1,5 +1,5 @@
-"""Compositions the paper builds from the same operations (Section 3.1: a module is recovered from M
-with L or MM; Section 3.4: global vs local memory sharing), expressed through the existing entry
+"""Compositions the paper builds from the same operations (Section 4.1: a module is recovered from M
+with L or MM; Section 4.2: global vs local memory sharing), expressed through the existing entry
 points and checked against the oracle:
   * a bias vector of length O is a one-row lookup (D = O) keyed by the module id;
   * local memory sharing is one M (and one dM) per module instead of one for all."""

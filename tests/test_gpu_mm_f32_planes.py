@@ -77,6 +77,38 @@ def test_f32_plane_products_match_oracle(roast, shape, pad):
     assert rel_err(to_host_f64(dM), oracle.mm_bwd_dm(h, 2, Z1, Z2, m, float(lam), Xo, dYo)) <= F32_TOL
 
 
+@pytest.mark.parametrize("same_sign", [True, False])
+def test_f32_plane_products_worst_case_mantissas(roast, same_sign):
+    """The three dropped plane products are largest when an operand's leading plane is minimal and its
+    two lower planes are all ones: significand 1.0000000 11111111 11111111b = 1 + 2^-7 - 2^-23.  Every
+    activation and every entry of M carries that significand (random exponents; with `same_sign` all
+    values positive, so the dropped terms add up instead of cancelling).  The bound is then
+    ~2^-20 of sum |x||w| per output, still inside the fp32 bar."""
+    I, H, O, Z1, Z2, m = 300, 512, 320, 64, 64, 30000
+    rng = np.random.default_rng(99)
+    worst = np.float32(1.0 + 2.0 ** -7 - 2.0 ** -23)
+    assert int(worst.view(np.uint32)) & 0x7fffff == 0xffff
+
+    def draw(shape, spread):
+        v = worst * np.exp2(rng.integers(-spread, spread + 1, size=shape)).astype(np.float32)
+        return v if same_sign else v * rng.choice(np.float32([-1.0, 1.0]), size=shape)
+
+    M, X, dY = draw(m, 2) * np.float32(0.05), draw((I, H), 3), draw((I, O), 3)
+    h = wl.draw_hash(rng, use_sign=not same_sign, align=1)
+    d = roast.mm_desc(H, O, Z1, Z2, m, 1, 1.0, h)
+    Md, Xd, dYd = to_dev(M), to_dev(X), to_dev(dY)
+    Y = roast.roast_mm_fwd(d, Xd, Md, ws=ws_tensor(roast.roast_mm_fwd_workspace(d, torch.float32, I)))
+    dX = roast.roast_mm_bwd_dx(d, dYd, Md, ws=ws_tensor(roast.roast_mm_bwd_dx_workspace(d, torch.float32, I)))
+    dM = torch.zeros(m, dtype=torch.float32, device="cuda")
+    roast.roast_mm_bwd_dM(d, Xd, dYd, dM, roast.ROAST_REDUCE_ATOMIC, ws_tensor(roast.roast_mm_bwd_dM_workspace_f32(d, I)))
+    torch.cuda.synchronize()
+    W = oracle.materialize_w(h, 1, H, O, Z1, Z2, 1.0, M)
+    Xo, dYo = X.astype(np.float64), dY.astype(np.float64)
+    assert rel_err(to_host_f64(Y), oracle.mm_fwd(Xo, W)) <= F32_TOL
+    assert rel_err(to_host_f64(dX), oracle.mm_bwd_dx(dYo, W)) <= F32_TOL
+    assert rel_err(to_host_f64(dM), oracle.mm_bwd_dm(h, 1, Z1, Z2, m, 1.0, Xo, dYo)) <= F32_TOL
+
+
 def test_plane_split_is_exact_on_awkward_values(roast):
     """With |M| one tile holding a single 1.0, one output column reproduces one input column: exactly
     for every value of magnitude >= 2^-100 (largest finite, just below a power of two, 24 significant

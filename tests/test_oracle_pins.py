@@ -1,6 +1,6 @@
 """Pins for the CPU oracle: checks against what the paper and plain mathematics fix, none of
-which go through the oracle's own arithmetic.  (arXiv 2207.10702: Section 3.1 mapping equations,
-Section 3.3 gradient equation, Theorem 1 / Appendix A.2 variance formula.)
+which go through the oracle's own arithmetic.  (arXiv 2207.10702: Section 4.1 mapping equations,
+Section 4.3 gradient equation, Theorem 1 / Appendix A.2 variance formula.)
 
 A mistake planted anywhere in the oracle (wrong in-tile stride, swapped tile coordinates, dropped
 sign or lambda, transposed operand, off-by-one range) is caught by at least one of:
