@@ -262,6 +262,28 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
                              roast_reduce_mode mode, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * roast_embed_bwd for callers that cannot allocate device memory and have no buffer to lend: code
+ * under HIP graph capture, tight serving / training loops with a fixed memory plan, harnesses that
+ * forbid hipMalloc.  Same arguments and results as roast_embed_bwd (both modes, same kernels), but
+ * the workspace is a 64 MiB array inside the library's code object instead of `ws`: the call neither
+ * allocates nor frees (no hipMalloc / hipFree, no allocating library routine) and takes no scratch.
+ *   - Limit: the bytes roast_embed_bwd_workspace(d, N, mode) reports must not exceed 64 MiB
+ *     (67 108 864); beyond that the call returns ROAST_ERR_WORKSPACE and launches nothing.  (ATOMIC:
+ *     about 16 bytes per chunk of the batch + 64 KiB per 4096 slots of M; DETERMINISTIC adds 8 bytes
+ *     per slot of M.  Config-4-sized M: up to ~690 000 lookups of 4 chunks per call.)
+ *   - Each GPU holds its own copy of the array from the moment the library's code is loaded on it
+ *     until the process ends.  The first call on a device looks its address up (once per device; do
+ *     that first call outside a graph capture, like every kernel's first launch).
+ *   - All calls on one GPU share that GPU's array, and it keeps the previous call's contents: the
+ *     call clears what must start at zero with fill kernels on `stream`.  Two such calls that overlap
+ *     in time on one GPU (different streams, or different host threads without ordering) race on the
+ *     array and give wrong gradients; calls ordered on one stream are safe.
+ */
+roast_status roast_embed_bwd_noalloc(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                                     const uint32_t* table_ids, const float* dOut, float* dM,
+                                     roast_reduce_mode mode, void* stream);
+
+/*
  * Pooled (bag-sum) lookup: the lookup L of Section 4.1 applied to every id of a bag, summed per bag
  * (the multi-hot use of an embedding table):
  *   out[b, :] = sum over n in [bag_offsets[b], bag_offsets[b+1]) of the row roast_embed_fwd returns

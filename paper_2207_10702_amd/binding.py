@@ -22,7 +22,7 @@ EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device",
            "roast_mm_fwd", "roast_mm_bwd_dx",
            "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
            "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_mm_bwd_dM",
-           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd",
+           "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd", "roast_embed_bwd_noalloc",
            "roast_embed_bag_fwd", "roast_embed_bag_bwd_workspace", "roast_embed_bag_bwd", "roast_optim_step"]
 
 
@@ -105,6 +105,7 @@ def load() -> C.CDLL:
     lib.roast_embed_bwd_workspace.argtypes = [EP, i64, i32]
     lib.roast_embed_bwd_workspace.restype = sz
     lib.roast_embed_bwd.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp, sz, vp]
+    lib.roast_embed_bwd_noalloc.argtypes = [EP, i64, vp, vp, vp, vp, i32, vp]
     lib.roast_embed_bag_fwd.argtypes = [EP, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.roast_embed_bag_bwd_workspace.argtypes = [EP, i64, i64, i32]
     lib.roast_embed_bag_bwd_workspace.restype = sz
@@ -371,6 +372,20 @@ def roast_embed_bwd(desc: RoastEmbedDesc, rows, table_ids, dOut, dM, mode: int =
                                   _vec(table_ids, torch.int32, "table_ids"), _vec(dOut, torch.float32, "dOut"),
                                   _vec(dM, torch.float32, "dM"), int(mode), wp, wb, _stream(stream)),
            "roast_embed_bwd")
+    return dM
+
+
+def roast_embed_bwd_noalloc(desc: RoastEmbedDesc, rows, table_ids, dOut, dM, mode: int = ROAST_REDUCE_ATOMIC,
+                            stream=None):
+    """roast_embed_bwd with the library's own static scratch array: no workspace, no allocation."""
+    torch = _torch()
+    N = rows.numel()
+    if tuple(dOut.shape) != (N, desc.D) or dM.numel() != desc.m_size:
+        raise ValueError("dOut must be N x D and dM must have m_size entries")
+    _check(load().roast_embed_bwd_noalloc(C.byref(desc), N, _vec(rows, torch.int64, "rows"),
+                                          _vec(table_ids, torch.int32, "table_ids"), _vec(dOut, torch.float32, "dOut"),
+                                          _vec(dM, torch.float32, "dM"), int(mode), _stream(stream)),
+           "roast_embed_bwd_noalloc")
     return dM
 
 

@@ -293,6 +293,19 @@ roast_status roast_embed_bwd(const roast_embed_desc* d, int64_t N, const int64_t
   return embed_bwd_atomic_launch(a, rows, table_ids, dOut, dM, ws, ws_bytes, (hipStream_t)stream);
 }
 
+roast_status roast_embed_bwd_noalloc(const roast_embed_desc* d, int64_t N, const int64_t* rows,
+                                     const uint32_t* table_ids, const float* dOut, float* dM,
+                                     roast_reduce_mode mode, void* stream) {
+  drop_stale_error();
+  EmbedArgs a;
+  roast_status st = make_embed_args(d, N, &a);
+  if (st != ROAST_OK) return st;
+  if (!mode_ok(mode)) return ROAST_ERR_ARG;
+  if (N == 0) return ROAST_OK;
+  if (!rows || !table_ids || !dOut || !dM) return ROAST_ERR_ARG;
+  return embed_bwd_static_run(a, rows, table_ids, dOut, dM, mode == ROAST_REDUCE_DETERMINISTIC, (hipStream_t)stream);
+}
+
 roast_status roast_embed_bag_fwd(const roast_embed_desc* d, int64_t N, int64_t B, const int64_t* rows,
                                  const uint32_t* table_ids, const int64_t* bag_offsets, const float* M, float* out,
                                  void* stream) {

@@ -802,6 +802,52 @@ roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const ui
   return hip_status(hipGetLastError());
 }
 
+// ---------------------------------------------------------------------------------------------
+// Lookup gradient for callers that cannot allocate: the workspace of roast_embed_bwd (bucket
+// cursors and lists; in the deterministic mode also the fixed-point accumulator) lives in a
+// file-scope device array instead of a caller buffer.  Every GPU the library runs on holds its own
+// copy of the array, at its own address, until the process ends.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each device, once known
+
+// Device address of this device's copy of `scratch` (in host code the array's name is only a
+// stand-in for the symbol, never an address a kernel could use).
+roast_status static_scratch_ptr(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ROAST_ERR_HIP;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return ROAST_ERR_HIP;
+    g_scratch_ptr[dev].store(p, std::memory_order_release);   // a race between host threads stores the same value twice
+  }
+  *out = p;
+  return ROAST_OK;
+}
+}  // namespace
+
+size_t embed_static_scratch_bytes() { return kStaticScratchBytes; }
+
+roast_status embed_bwd_static_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
+                                  float* dM, bool deterministic, hipStream_t s) {
+  const size_t need = deterministic ? embed_det_workspace_bytes(a) : embed_bucket_workspace_bytes(a);
+  if (deterministic && need == 0) return ROAST_ERR_UNSUPPORTED;
+  if (need > kStaticScratchBytes) return ROAST_ERR_WORKSPACE;
+  void* ws = nullptr;
+  if (need > 0) {
+    const roast_status st = static_scratch_ptr(&ws);
+    if (st != ROAST_OK) return st;
+  }
+  // From here on the device pointer `ws` stands for the array: the kernels get it as an argument,
+  // exactly as they get the caller's buffer in roast_embed_bwd.  What has to start at zero (bucket
+  // cursors, the fixed-point accumulator and its scale record) is cleared by fill kernels inside.
+  if (deterministic) return embed_bwd_det_run(a, rows, tables, dOut, dM, ws, s);
+  return embed_bwd_atomic_launch(a, rows, tables, dOut, dM, ws, need, s);
+}
+
 roast_status embed_bag_fwd_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* M,
                                   float* out, hipStream_t s) {
   if (a.m_size >= (1ll << 31) || a.C > kMaxC || a.hash.use_sign == 2) {

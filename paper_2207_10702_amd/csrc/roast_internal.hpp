@@ -148,6 +148,11 @@ roast_status embed_bwd_atomic_launch(const EmbedArgs& a, const int64_t* rows, co
 size_t embed_det_workspace_bytes(const EmbedArgs& a);
 roast_status embed_bwd_det_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
                                float* dM, void* ws, hipStream_t s);
+// the same gradient with its workspace in a static device array (no caller buffer); WORKSPACE when
+// the call needs more than embed_static_scratch_bytes()
+size_t embed_static_scratch_bytes();
+roast_status embed_bwd_static_run(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, const float* dOut,
+                                  float* dM, bool deterministic, hipStream_t s);
 roast_status optim_launch(const roast_optim_desc& d, int64_t m_size, float* M, float* dM, float* st1, float* st2,
                           void* shadow, hipStream_t s);
 roast_status chunk_index_launch(const EmbedArgs& a, const int64_t* rows, const uint32_t* tables, int64_t* off,
