@@ -287,15 +287,21 @@ def bench_dim_sweep(args, roast, wl, torch, np):
             row["roast"][f"{m * 4 >> 20}MB"] = r
             del ws
         # element-wise hashing (1x1 tiles, one hash per virtual weight): the HashedNet-style map the
-        # paper compares against, run through the same entry points (generic kernels)
+        # paper compares against, through the same entry points and the same matrix-core kernels -- only
+        # the staging of the weight operand differs (a gather through the hash per element instead of a
+        # contiguous tile) -- with the same split-contraction workspace (bf16; fp32 runs it on the
+        # vector ALUs)
         row["elementwise_1x1"] = {}
         for m in (m_sizes[0], m_sizes[-1]):
             d = roast.mm_desc(dim, dim, 1, 1, m, 0, 1.0, hp)
             M, dMv = Ms[m], dM[:m]
+            nbytes = max(roast.roast_mm_fwd_workspace(d, tdt, I), roast.roast_mm_bwd_dx_workspace(d, tdt, I), 16)
+            ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
             row["elementwise_1x1"][f"{m * 4 >> 20}MB"] = {
-                "fwd_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y), 3, 1),
-                "dx_ms": timed(lambda: roast.roast_mm_bwd_dx(d, dY, M, dX), 3, 1),
+                "fwd_ms": timed(lambda: roast.roast_mm_fwd(d, X, M, Y, ws=ws), 3, 1),
+                "dx_ms": timed(lambda: roast.roast_mm_bwd_dx(d, dY, M, dX, ws=ws), 3, 1),
                 "dM_ms": timed(lambda: roast.roast_mm_bwd_dM(d, X, dY, dMv, roast.ROAST_REDUCE_ATOMIC), 3, 1)}
+            del ws
         rows.append(row)
         print(f"# Dim {dim}: dense fwd {row['dense_fwd_ms']:.3f} ms; ROAST fwd "
               + " / ".join(f"{v['fwd_ms']:.3f}" for v in row["roast"].values()) + " ms; 1x1 tiles fwd "

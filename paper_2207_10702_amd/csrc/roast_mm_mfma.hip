@@ -34,6 +34,7 @@
 // contiguous band of output row blocks.
 #include <atomic>
 #include <type_traits>
+#include <utility>
 
 #include "roast_internal.hpp"
 
@@ -103,6 +104,7 @@ struct KernArgs {
   int rows_per_split;  // length of one part of the contraction axis (DM always; FWD / DX when nbz > 1)
   int split_begin[18]; // dM with uneven parts (all zero: unused): part z covers rows [split_begin[z], split_begin[z+1])
   int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
+  int y_fastest;       // block order inside a contraction part: 0 = x fastest (forward / dX), 1 = y fastest (dM)
 };
 
 // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Blocks that share
@@ -116,8 +118,16 @@ __device__ inline bool block_coords(const KernArgs& p, int* bx, int* by, int* bz
   const int w = blockIdx.x;
   const int t = (w & 7) * chunk + (w >> 3);
   if ((w >> 3) >= chunk || t >= total) return false;
-  *bx = t % p.nbx;
-  *by = (t / p.nbx) % p.nby;
+  if (p.y_fastest) {
+    // dM: the row blocks (y, along H) of one column block and contraction part are neighbours, so
+    // that the workgroups of an XCD share their dY slabs (the large operand) completely and each X
+    // slab is fetched by as few L2s as possible
+    *by = t % p.nby;
+    *bx = (t / p.nby) % p.nbx;
+  } else {
+    *bx = t % p.nbx;
+    *by = (t / p.nbx) % p.nby;
+  }
   *bz = t / (p.nbx * p.nby);
   return true;
 }
@@ -185,7 +195,29 @@ struct ProdCtx {
   int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
   // DM: 8(k) x CW blocks of both operands; thread -> column block ptid & 31, k-block ptid >> 5
   int ta_col, tb_col;
+  // ELEM (forward / dX, one hash per virtual weight): thread -> LDS row ptid & 127 (one output
+  // column: the "fixed" coordinate) and half ptid >> 7 of the 64-deep step (32 consecutive values of
+  // the contraction index: the "running" coordinate).  el_u / el_s: the fixed coordinate's part of
+  // the offset hash and of the sign hash; el_inner: its part of the offset inside the tile.
+  uint32_t el_u, el_s;
+  int el_inner;
 };
+
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>): a loop whose index is a constant expression
+template <typename F, int... Is>
+__device__ inline void static_for_impl(F&& f, std::integer_sequence<int, Is...>) {
+  (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F>
+__device__ inline void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// (a + b) mod P for a, b < P < 2^32
+__device__ inline uint32_t addmod32(uint32_t a, uint32_t b, uint32_t P) {
+  const uint32_t s = a + b;
+  return (s < a || s >= P) ? s - P : s;
+}
 
 template <int MODE, int BM, int BN, bool SHADOW>
 struct RegSet {
@@ -200,6 +232,12 @@ struct RegSet {
   uint4v ds_reg[(MODE == MODE_DX && SHADOW) ? Ctx::DX_LOADS : 1];
 };
 
+// ELEM: 32 gathered weights of one output column and one bit of sign each
+struct ElemRegs {
+  float w[32];
+  uint32_t neg;
+};
+
 
 // X3: fp32 in, fp32 out on the bf16 matrix cores.  Every fp32 operand value x is held as three
 // bfloat16 planes with x = hi + mid + lo exactly (3 x 8 significand bits); a product x*w is the sum
@@ -209,9 +247,15 @@ struct RegSet {
 // all ones) and are near 2^-24 |x||w| for typical mantissas; the accumulation is the usual fp32 one.  The contraction loop simply runs six times as many steps: step = 6*kq + pair.
 // RAGK: the contraction length of forward / dX is a multiple of 8 but not of 64 (a separate
 // instantiation: the extra selects in the load waves cost the regular kernels 15 %).
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false>
+// ELEM: one hash per virtual weight instead of one per tile.  Forward / dX: the weight producers
+// gather every element of their 64 x 128 slab of W from M through the hash (any tile size down to
+// 1 x 1, per-tile or per-element sign), round it and stage it like the tiled kernels do, so the same
+// consumers run; dM: the epilogue hashes every accumulator element to its slot.  This is the
+// element-wise (HashedNet-style) map of Section 3 run at the same arithmetic as the tiled map.
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false, bool ELEM = false>
 __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p) {
   static_assert(!X3 || SHADOW || MODE == MODE_DM, "the plane kernels read the weight planes, not fp32 M");
+  static_assert(!ELEM || (!SHADOW && !X3 && BN == 128 && (RAGK || MODE == MODE_DM)), "element-wise staging: fp32 M, 128-wide blocks, any contraction length");
   constexpr int NC = WGM * WGN;                  // consumer waves
   // Eight producer waves follow the consumers: waves NC..NC+3 bring in the A operand (forward / dX:
   // direct-to-LDS loads of the activations; dM: X transposed through registers), waves NC+4..NC+7
@@ -290,6 +334,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     }
     constexpr int NB = ADMA ? NT - 256 : NT;     // threads that build the table
     const int bi = (ADMA && wave >= NC) ? tid - 256 : tid;
+    if (ELEM) cnt = 0;                           // no tile table: every element is hashed where it is used
     for (int e = dma_wave ? cnt : bi; e < cnt; e += NB) {
       uint64_t x, y;
       if (MODE == MODE_FWD) { x = e / TN; y = y0 + e % TN; }
@@ -371,6 +416,69 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       c.ta_col = min(m0 + (pt & 31) * (BM / 32), (int)a.H - BM / 32);
       c.tb_col = min(n0 + (pt & 31) * (BN / 32), (int)a.O - BN / 32);
     }
+    // ELEM.  W[i, j] sits at offset(x, y) + Z2 * (i mod Z1) + (j mod Z2), x = i / Z1, y = j / Z2, with
+    // sign g(x, y) or g(i, j).  The hash of a key is a sum of per-coordinate terms mod P, so a thread
+    // keeps the terms of its fixed coordinate (forward: j = its output column; dX: i = its output
+    // column) and walks the running coordinate (the contraction index) with adds.
+    constexpr bool EL_FWD = MODE == MODE_FWD;
+    const uint32_t el_P = (uint32_t)a.hash.P.d;
+    const int el_zrun = EL_FWD ? a.Z1 : a.Z2;                                  // tile extent along the running coordinate
+    const uint32_t el_ca = (uint32_t)(EL_FWD ? a.hash.a1 : a.hash.a2);         // offset-hash coefficient of the running tile index
+    const uint32_t el_cs = (uint32_t)(EL_FWD ? a.hash.s1 : a.hash.s2);         // sign-hash coefficient of the running index
+    if constexpr (ELEM && MODE != MODE_DM) {
+      const int f = min(n0 + (pt & 127), Ndim - 1);
+      const int zf = EL_FWD ? a.Z2 : a.Z1;
+      const uint64_t tf = (uint64_t)(f / zf), L = bmod(a.layer, a.hash.P);
+      c.el_u = (uint32_t)bmod(bmod(a.hash.a0 * L, a.hash.P) + bmod((EL_FWD ? a.hash.a2 : a.hash.a1) * tf, a.hash.P) + a.hash.a3,
+                              a.hash.P);
+      const uint64_t sk = a.hash.use_sign == 2 ? (uint64_t)f : tf;             // element sign: keyed by the coordinate itself
+      c.el_s = (uint32_t)bmod(bmod(a.hash.s0 * L, a.hash.P) + bmod((EL_FWD ? a.hash.s2 : a.hash.s1) * sk, a.hash.P) + a.hash.s3,
+                              a.hash.P);
+      c.el_inner = EL_FWD ? f % zf : a.Z2 * (f % zf);
+    }
+    [[maybe_unused]] auto elem_load = [&](ElemRegs& r, int step) {
+      const int t0 = step_k0(step) + 32 * (pt >> 7);                           // first running index of this thread
+      const int tile0 = t0 / el_zrun;
+      int rem = t0 - tile0 * el_zrun;
+      uint32_t run_u = (uint32_t)bmod((uint64_t)el_ca * (uint64_t)tile0, a.hash.P);
+      uint32_t run_s = a.hash.use_sign == 0 ? 0u
+                       : (uint32_t)bmod((uint64_t)el_cs * (uint64_t)(a.hash.use_sign == 2 ? t0 : tile0), a.hash.P);
+      const int inner_mul = EL_FWD ? a.Z2 : 1;
+      uint32_t neg = 0u;
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int e = 0; e < 32; ++e) {
+        const uint32_t u = addmod32(c.el_u, run_u, el_P);
+        const int64_t idx = (int64_t)((uint64_t)a.hash.align * mod_slots32(a.hash, u)) + c.el_inner + inner_mul * rem;
+        r.w[e] = p.M[(t0 + e < k_end) ? idx : 0];                              // beyond the contraction: any valid slot, zeroed below
+        if (a.hash.use_sign != 0) neg |= (addmod32(c.el_s, run_s, el_P) & 1u) << e;
+        ++rem;
+        const bool wrap = rem == el_zrun;
+        rem = wrap ? 0 : rem;
+        run_u = wrap ? addmod32(run_u, el_ca, el_P) : run_u;
+        if (a.hash.use_sign == 2 || (a.hash.use_sign == 1 && wrap)) run_s = addmod32(run_s, el_cs, el_P);
+      }
+      r.neg = neg;
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    [[maybe_unused]] auto elem_store = [&](ElemRegs& r, int step) {
+      char* Bt = b_stage(step);
+      const int t0 = step_k0(step) + 32 * (pt >> 7);
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        uint4v o;
+#pragma unroll
+        for (int pr = 0; pr < 4; ++pr) {
+          const int e0 = 8 * cc + 2 * pr;
+          float v0 = (r.neg >> e0) & 1u ? -r.w[e0] : r.w[e0];
+          float v1 = (r.neg >> (e0 + 1)) & 1u ? -r.w[e0 + 1] : r.w[e0 + 1];
+          if (t0 + e0 >= k_end) v0 = 0.f;
+          if (t0 + e0 + 1 >= k_end) v1 = 0.f;
+          o[pr] = pack_bf16x2(v0, v1);
+        }
+        *reinterpret_cast<uint4v*>(Bt + lds_off(pt & 127, 4 * (pt >> 7) + cc)) = o;
+      }
+    };
 
     auto load_global = [&](RegSet<MODE, BM, BN, SHADOW>& r, int step) {
       const int k0 = step_k0(step);
@@ -555,6 +663,30 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       __builtin_amdgcn_s_barrier();
       return;
     }
+    if constexpr (ELEM) {
+      // the same two-deep pipeline as below with the gathered registers
+      ElemRegs er[2];
+      const int lastE = nsteps - 1;
+      if (nsteps > 0) {
+        elem_load(er[0], 0);
+        elem_load(er[1], min(1, lastE));
+      }
+      int sE = 0;
+      for (; sE + 2 <= nsteps; sE += 2) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          elem_store(er[j], sE + j);
+          elem_load(er[j], min(sE + j + 2, lastE));
+          __syncthreads();                               // barrier sE + j
+        }
+      }
+      if (sE < nsteps) {
+        elem_store(er[0], sE);
+        __syncthreads();
+      }
+      __syncthreads();                                   // pairs with the consumers' barrier before the epilogue
+      return;
+    }
     RegSet<MODE, BM, BN, SHADOW> rs[NSETS];
     const int last = nsteps - 1;
     if (nsteps > 0) {
@@ -718,6 +850,43 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   } else {
     // acc[i][j][e]: row (h) = 8*(e/4) + 4*(lane >> 5) + e%4, column (o) = lane & 31 inside the block
     const int lr = 4 * (lane >> 5), lc = lane & 31;
+    if constexpr (ELEM) {
+      if (p.G == nullptr) {
+        // One hash per accumulator element: the column's terms of the two hashes once per 32 x 32
+        // block, the row's per element.  (Indices are compile-time constants throughout, so the
+        // accumulators stay in registers however large this gets.)
+        const uint32_t P32 = (uint32_t)a.hash.P.d;
+        const uint64_t L = bmod(a.layer, a.hash.P);
+        static_for<MI * NI>([&](auto IJ) {
+          constexpr int i = decltype(IJ)::value / NI, j = decltype(IJ)::value % NI;
+          const int hb = m0 + wm * WTM + i * 32, ob = n0 + wn * WTN + j * 32;
+          const int o = ob + lc;
+          const int oc = min(o, (int)a.O - 1);
+          const uint64_t y = (uint64_t)(oc / a.Z2);
+          const int oin = oc % a.Z2;
+          const uint32_t col_u = (uint32_t)bmod(bmod(a.hash.a0 * L, a.hash.P) + bmod(a.hash.a2 * y, a.hash.P) + a.hash.a3, a.hash.P);
+          const uint32_t col_s = (uint32_t)bmod(bmod(a.hash.s0 * L, a.hash.P) +
+                                                bmod(a.hash.s2 * (a.hash.use_sign == 2 ? (uint64_t)oc : y), a.hash.P) + a.hash.s3,
+                                                a.hash.P);
+          static_for<16>([&](auto E) {
+            constexpr int e = decltype(E)::value;
+            const int h = hb + 8 * (e >> 2) + lr + (e & 3);
+            const int hc = min(h, (int)a.H - 1);
+            const uint64_t x = (uint64_t)(hc / a.Z1);
+            const int hin = hc % a.Z1;
+            const uint32_t u = addmod32(col_u, (uint32_t)bmod(a.hash.a1 * x, a.hash.P), P32);
+            float sc = a.lambda;
+            if (a.hash.use_sign != 0) {
+              const uint64_t key = a.hash.use_sign == 2 ? (uint64_t)hc : x;
+              if (addmod32(col_s, (uint32_t)bmod(a.hash.s1 * key, a.hash.P), P32) & 1u) sc = -sc;
+            }
+            float* d = p.dM + (int64_t)((uint64_t)a.hash.align * mod_slots32(a.hash, u)) + (int64_t)a.Z2 * hin + oin;
+            if (h < (int)a.H && o < (int)a.O) unsafeAtomicAdd(d, sc * acc[i][j][e]);
+          });
+        });
+        return;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -754,23 +923,24 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
 template <int MODE, int BM, int BN>
 constexpr int smem_bytes() { return ((MODE != MODE_DM ? 3 : 2) * BM + 2 * BN) * 128 + kMaxTable * 12; }
 
-template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false>
+template <int MODE, int BM, int BN, int WGM, int WGN, bool SHADOW, bool X3 = false, bool RAGK = false, bool ELEM = false>
 roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
   p.nbx = (int)blocks.x; p.nby = (int)blocks.y; p.nbz = (int)blocks.z;
+  p.y_fastest = MODE == MODE_DM ? 1 : 0;
   const dim3 grid((unsigned)((total + 7) / 8 * 8));
   constexpr int smem = smem_bytes<MODE, BM, BN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
   static std::atomic<bool> configured{false};   // per instantiation and process; a race between host threads only repeats the call
   if (!configured.load(std::memory_order_acquire)) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void*>(&k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK, ELEM>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return ROAST_ERR_HIP;
     configured.store(true, std::memory_order_release);
   }
-  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK>), grid, dim3((WGM * WGN + 8) * 64), smem, s,
-                     p);
+  hipLaunchKernelGGL((k_roast_mfma<MODE, BM, BN, WGM, WGN, SHADOW, X3, RAGK, ELEM>), grid, dim3((WGM * WGN + 8) * 64),
+                     smem, s, p);
   return hip_status(hipGetLastError());
 }
 
@@ -953,7 +1123,8 @@ roast_status shadow3(const float* M, int64_t m_size, uint16_t* out, hipStream_t 
   return hip_status(hipGetLastError());
 }
 
-// (the tile table holds one sign per tile: per-element signs, use_sign == 2, go to the generic kernels)
+// (the tile table holds one sign per tile: per-element signs, use_sign == 2, and tiles that break the
+// rules below take the element-wise instantiations, one hash per virtual weight)
 // The contraction runs in 64-deep steps; its length (H resp. O) only has to be a multiple of 8: the
 // last step's surplus is staged as zero weights.  A load thread's block of the weight tile -- 8 rows of the contraction axis (forward), 8 consecutive elements of it (dX) --
 // must lie inside one hash tile, which may be smaller than the step.
@@ -965,19 +1136,22 @@ bool mfma_dx_ok(const MMArgs& a) {
   return a.hash.use_sign != 2 && a.Z2 % 8 == 0 && a.O % 8 == 0 && a.H % 8 == 0 &&
          a.nTy * (cdiv(kBN, a.Z1) + 1) <= kMaxTable;
 }
+// element-wise staging: any tile shape and sign mode; the activations still go to LDS in 16-byte pieces
+bool mfma_elem_ok(const MMArgs& a) { return a.H % 8 == 0 && a.O % 8 == 0; }
 
 }  // namespace
 
 int mfma_fwd_splits(const MMArgs& a) {
-  return mfma_fwd_ok(a) ? mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), a.H) : 1;
+  return (mfma_fwd_ok(a) || mfma_elem_ok(a)) ? mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), a.H) : 1;
 }
 int mfma_dx_splits(const MMArgs& a) {
-  return mfma_dx_ok(a) ? mm_pick_splits(cdiv(a.H, kBN) * cdiv(a.I, kBM), a.O) : 1;
+  return (mfma_dx_ok(a) || mfma_elem_ok(a)) ? mm_pick_splits(cdiv(a.H, kBN) * cdiv(a.I, kBM), a.O) : 1;
 }
 
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
                          int64_t ldy, float* ws, hipStream_t s) {
-  if (!mfma_fwd_ok(a) || ldx % 8 != 0 || ldy % 8 != 0 || !aligned16(X) || !aligned16(Y))
+  const bool elem = !mfma_fwd_ok(a);
+  if ((elem && !mfma_elem_ok(a)) || ldx % 8 != 0 || ldy % 8 != 0 || !aligned16(X) || !aligned16(Y))
     return ROAST_ERR_UNSUPPORTED;
   constexpr int BM = kBM, BN = kBN;
   KernArgs p{};
@@ -989,8 +1163,10 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   const bool shadow = M_bf16 && a.Z2 % 8 == 0;
   roast_status st;
   // a narrower block (256 x 96, eight 32 x 96 consumer tiles) when it fills the CUs better
-  const bool narrow = shadow && a.H % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.O);
-  if (narrow) {
+  const bool narrow = !elem && shadow && a.H % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.O);
+  if (elem) {
+    st = launch<MODE_FWD, BM, BN, 4, 2, false, false, true, true>(p, grid, s);
+  } else if (narrow) {
     grid.x = (unsigned)cdiv(a.O, kBNarrow);
     st = launch<MODE_FWD, BM, kBNarrow, 8, 1, true>(p, grid, s);
   } else if (a.H % BK != 0)
@@ -1003,7 +1179,8 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
 
 roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const float* M, const void* M_bf16,
                             void* dX, int64_t ldx, float* ws, hipStream_t s) {
-  if (!mfma_dx_ok(a) || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) || !aligned16(dX))
+  const bool elem = !mfma_dx_ok(a);
+  if ((elem && !mfma_elem_ok(a)) || ldy % 8 != 0 || ldx % 8 != 0 || !aligned16(dY) || !aligned16(dX))
     return ROAST_ERR_UNSUPPORTED;
   constexpr int BM = kBM, BN = kBN;
   KernArgs p{};
@@ -1012,8 +1189,10 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   dim3 grid((unsigned)cdiv(a.H, BN), (unsigned)cdiv(a.I, BM), 1);
   split_setup(&p, &grid, a.O, mfma_dx_splits(a), ws);
   roast_status st;
-  const bool narrow = M_bf16 && a.O % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.H);
-  if (narrow) {
+  const bool narrow = !elem && M_bf16 && a.O % BK == 0 && grid.z == 1 && narrow_pays(cdiv(a.I, BM), a.H);
+  if (elem) {
+    st = launch<MODE_DX, BM, BN, 4, 2, false, false, true, true>(p, grid, s);
+  } else if (narrow) {
     grid.x = (unsigned)cdiv(a.H, kBNarrow);
     st = launch<MODE_DX, BM, kBNarrow, 8, 1, true>(p, grid, s);
   } else if (a.O % BK != 0)
@@ -1047,12 +1226,14 @@ static void uneven_parts(int64_t I, int splits, int* begin) {
 roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const void* dY, int64_t ldy, float* dM,
                             float* Gws, int splits, hipStream_t s) {
   constexpr int BM = 256, BN = 128;
-  if (a.Z1 % 4 != 0 || a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 ||
-      !aligned16(X) || !aligned16(dY) || a.H < BM / 32 || a.O < BN / 32)
+  if (a.H % 8 != 0 || a.O % 8 != 0 || ldx % 8 != 0 || ldy % 8 != 0 || !aligned16(X) || !aligned16(dY) ||
+      a.H < BM / 32 || a.O < BN / 32)
     return ROAST_ERR_UNSUPPORTED;
-  // the atomic epilogue applies one sign per tile; raw products for the deterministic reduction are sign-free
-  if (Gws == nullptr && a.hash.use_sign == 2) return ROAST_ERR_UNSUPPORTED;
-  if ((cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable) return ROAST_ERR_UNSUPPORTED;
+  // The tiled epilogue looks a tile up once per four accumulator rows and applies one sign per tile;
+  // other tile shapes, per-element signs and tile tables that do not fit hash every element instead
+  // (raw products for the deterministic reduction carry no sign and need no table either way).
+  const bool elem = a.Z1 % 4 != 0 || (Gws == nullptr && a.hash.use_sign == 2) ||
+                    (cdiv(BM, a.Z1) + 1) * (cdiv(BN, a.Z2) + 1) > kMaxTable;
   const int64_t tiles = cdiv(a.H, BM) * cdiv(a.O, BN);
   if (Gws == nullptr) splits = dm_pick_splits(tiles, a.I, a.H * a.O);
   if (splits < 1 || splits > 65535) return ROAST_ERR_UNSUPPORTED;
@@ -1063,7 +1244,8 @@ roast_status mfma_mm_bwd_dM(const MMArgs& a, const void* X, int64_t ldx, const v
   p.rows_per_split = (int)rows;
   if (Gws == nullptr) uneven_parts(a.I, splits, p.split_begin);
   const dim3 grid((unsigned)cdiv(a.O, BN), (unsigned)cdiv(a.H, BM), (unsigned)splits);
-  return launch<MODE_DM, BM, BN, 4, 2, false>(p, grid, s);
+  return elem ? launch<MODE_DM, BM, BN, 4, 2, false, false, false, true>(p, grid, s)
+              : launch<MODE_DM, BM, BN, 4, 2, false>(p, grid, s);
 }
 
 // ---- fp32 through the three-plane kernels.  Workspace layout (every part 256-byte aligned):

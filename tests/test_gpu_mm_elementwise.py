@@ -1,0 +1,79 @@
+"""GPU parity of the element-wise instantiations of the matrix-core kernels (one hash per virtual
+weight): 1 x 1 tiles -- the HashedNet-style map of Section 3 (Background) that the paper compares
+against --, tile shapes the tiled kernels do not take (7 x 5, 3 x 64), and the per-element reading of
+the sign map g (end of Section 4.1) on ordinary tiles.  bf16 activations; forward, dX, dM in both
+reduce modes against the oracle, over several workgroup blocks, ragged rows / columns / contraction
+lengths, a split contraction, a 32-bit prime, aligned offsets and no sign."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2207_10702_amd import workloads as wl
+from tests.util import BF16_TOL, rel_err, to_dev, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+P32 = 4294967291          # largest prime below 2^32: sums of two residues wrap 32 bits
+
+# I, H, O, Z1, Z2, |M|, use_sign, align, P
+CASES = [
+    (300, 128, 320, 1, 1, 5000, 1, 1, None),          # element-wise hashing, sign per element (= per tile)
+    (520, 200, 136, 1, 1, 300000, 1, 1, None),        # ragged contraction (200 = 3 x 64 + 8), ragged last column block
+    (300, 128, 320, 7, 5, 20000, 1, 1, None),         # tiles that divide nothing
+    (300, 256, 128, 64, 64, 30000, 2, 1, None),       # ordinary tiles, sign per element
+    (513, 192, 136, 16, 8, 7000, 2, 1, None),         # small tiles, sign per element, one row past two row blocks
+    (2100, 256, 128, 3, 64, 30000, 1, 1, None),       # dM: tile rows not a multiple of 4; contraction split over workgroups
+    (64, 2048, 1024, 1, 1, 50000, 1, 1, None),        # small batch: forward / dX with a split contraction (workspace)
+    (300, 128, 320, 1, 1, 5000, 1, 3, P32),           # 32-bit prime, offsets in multiples of 3
+    (257, 64, 128, 5, 3, 4096, 0, 1, P32),            # no sign
+    (300, 128, 320, 1, 1, 1, 2, 1, None),             # |M| == 1: every virtual weight is +-M[0]
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_elementwise_mfma_kernels_match_oracle(roast, case):
+    I, H, O, Z1, Z2, m, use_sign, align, P = case
+    rng = np.random.default_rng(900 + I + Z1 + m % 97)
+    M = wl.draw_m(rng, m, ("normal", 0.05))
+    X, dY = wl.draw_act(rng, I, H, "bf16"), wl.draw_act(rng, I, O, "bf16")
+    h = wl.draw_hash(rng, use_sign=bool(use_sign), align=align, **({"P": P} if P else {}))
+    h["use_sign"] = use_sign
+    lam = np.float32(0.7)
+    d = roast.mm_desc(H, O, Z1, Z2, m, 9, lam, h)
+    Md, Xd, dYd = to_dev(M), to_dev(X), to_dev(dY)
+    nf, nx = roast.roast_mm_fwd_workspace(d, torch.bfloat16, I), roast.roast_mm_bwd_dx_workspace(d, torch.bfloat16, I)
+    if I <= 64:
+        assert nf > 0 and nx > 0                       # the split contraction is offered to these kernels too
+    ws = torch.empty(max(nf, nx, 16), dtype=torch.uint8, device="cuda")
+    Y = roast.roast_mm_fwd(d, Xd, Md, ws=ws if nf else None)
+    dX = roast.roast_mm_bwd_dx(d, dYd, Md, ws=ws if nx else None)
+    dM = torch.zeros(m, dtype=torch.float32, device="cuda")
+    roast.roast_mm_bwd_dM(d, Xd, dYd, dM)
+    det = roast.ROAST_REDUCE_DETERMINISTIC
+    n_tiles = -(-H // Z1) * -(-O // Z2)
+    dM_det = None
+    if n_tiles <= 1 << 17:                             # the deterministic mode ranks at most 2^17 tiles per layer
+        wd = torch.empty(max(roast.roast_mm_bwd_dM_workspace(d, I, det), 1), dtype=torch.uint8, device="cuda")
+        dM_det = torch.zeros(m, dtype=torch.float32, device="cuda")
+        roast.roast_mm_bwd_dM(d, Xd, dYd, dM_det, det, wd)
+    else:
+        assert roast.roast_mm_bwd_dM_workspace(d, I, det) == 0
+    torch.cuda.synchronize()
+    W = oracle.materialize_w(h, 9, H, O, Z1, Z2, float(lam), M)
+    Xo, dYo = wl.act_as_f64(X), wl.act_as_f64(dY)
+    assert rel_err(to_host_f64(Y), oracle.mm_fwd(Xo, W)) <= BF16_TOL
+    assert rel_err(to_host_f64(dX), oracle.mm_bwd_dx(dYo, W)) <= BF16_TOL
+    ref = oracle.mm_bwd_dm(h, 9, Z1, Z2, m, float(lam), Xo, dYo)
+    assert rel_err(to_host_f64(dM), ref) <= BF16_TOL
+    if dM_det is not None:
+        assert rel_err(to_host_f64(dM_det), ref) <= BF16_TOL
+    # strided rows (leading dimension > columns) through the same kernels
+    pad = 8
+    Xp = torch.zeros((I, H + pad), dtype=torch.bfloat16, device="cuda")[:, :H]
+    Xp.copy_(Xd)
+    Yp = torch.full((I, O + pad), 3.0, dtype=torch.bfloat16, device="cuda")[:, :O]
+    roast.roast_mm_fwd(d, Xp, Md, Yp)
+    torch.cuda.synchronize()
+    assert torch.equal(Yp, roast.roast_mm_fwd(d, Xd, Md)) and torch.all(Yp._base[:, O:] == 3.0)

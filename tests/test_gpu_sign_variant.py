@@ -1,6 +1,7 @@
 """GPU parity of the per-element sign variant (use_sign = 2) against the oracle: ROAST-MM forward,
-dX, dM (atomic and deterministic) in fp32 and bf16 -- including shapes the matrix-core kernels would
-otherwise take, which must fall back -- and the lookup, its gradient and the pooled lookup."""
+dX, dM (atomic and deterministic) in fp32 and bf16 -- on shapes the tiled matrix-core kernels would
+otherwise take (bf16: their element-wise instantiations run instead; fp32: the vector-ALU kernels)
+and on shapes only the generic kernels take -- and the lookup, its gradient and the pooled lookup."""
 import numpy as np
 import pytest
 
@@ -33,7 +34,7 @@ def test_mm_per_element_sign(roast, shape, dtype, tol):
     Md, Xd, dYd = to_dev(M), to_dev(X), to_dev(dY)
     wsz = max(roast.roast_mm_fwd_workspace(d, Xd.dtype, I), roast.roast_mm_bwd_dx_workspace(d, Xd.dtype, I),
               roast.roast_mm_bwd_dM_workspace(d, I, roast.ROAST_REDUCE_ATOMIC), roast.roast_mm_bwd_dM_workspace_f32(d, I))
-    assert wsz == 0                                        # no fast path claims this variant
+    assert wsz == 0                                        # no workspace helps these sizes in this variant
     shadow = roast.roast_m_shadow_bf16(Md) if dtype == "bf16" else None
     Y = roast.roast_mm_fwd(d, Xd, Md, M_bf16=shadow)
     dX = roast.roast_mm_bwd_dx(d, dYd, Md, M_bf16=shadow)
