@@ -104,7 +104,6 @@ struct KernArgs {
   int rows_per_split;  // length of one part of the contraction axis (DM always; FWD / DX when nbz > 1)
   int split_begin[18]; // dM with uneven parts (all zero: unused): part z covers rows [split_begin[z], split_begin[z+1])
   int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
-  int y_fastest;       // block order inside a contraction part: 0 = x fastest (forward / dX), 1 = y fastest (dM)
 };
 
 // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Blocks that share
@@ -118,16 +117,8 @@ __device__ inline bool block_coords(const KernArgs& p, int* bx, int* by, int* bz
   const int w = blockIdx.x;
   const int t = (w & 7) * chunk + (w >> 3);
   if ((w >> 3) >= chunk || t >= total) return false;
-  if (p.y_fastest) {
-    // dM: the row blocks (y, along H) of one column block and contraction part are neighbours, so
-    // that the workgroups of an XCD share their dY slabs (the large operand) completely and each X
-    // slab is fetched by as few L2s as possible
-    *by = t % p.nby;
-    *bx = (t / p.nby) % p.nbx;
-  } else {
-    *bx = t % p.nbx;
-    *by = (t / p.nbx) % p.nby;
-  }
+  *bx = t % p.nbx;
+  *by = (t / p.nbx) % p.nby;
   *bz = t / (p.nbx * p.nby);
   return true;
 }
@@ -928,7 +919,6 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
   p.nbx = (int)blocks.x; p.nby = (int)blocks.y; p.nbz = (int)blocks.z;
-  p.y_fastest = MODE == MODE_DM ? 1 : 0;
   const dim3 grid((unsigned)((total + 7) / 8 * 8));
   constexpr int smem = smem_bytes<MODE, BM, BN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
