@@ -356,8 +356,8 @@ roast_status launch_embed(const EmbedArgs& a, const int64_t* rows, const uint32_
 constexpr int kSeg = 8192;          // chunks per accumulate workgroup
 constexpr int kMaxBuckets = 2048;
 constexpr int kMaxR = 8192;         // largest bucket (slots); its fp64 LDS image is (kMaxR + Z) * 8 bytes, up to 72 KiB
-constexpr int kRouteItems = 4096;   // chunks per route workgroup (lookups per workgroup = kRouteItems / C)
-constexpr int kRouteThreads = 256;
+constexpr int kRouteItems = 8192;   // chunks per route workgroup (lookups per workgroup = kRouteItems / C)
+constexpr int kRouteThreads = 512;
 
 struct BucketPlan {
   bool ok;
