@@ -421,7 +421,8 @@ def main():
         section(1)
         if not args.mm_only:
             roast.roast_embed_fwd(ed, rows, tables, eM, out); mark()
-            section(2)
+        section(2)
+        if not args.mm_only:
             roast.roast_embed_bwd(ed, rows, tables, dOut, edM, mode, ews); mark()
         section(3)
         if cal_src is not None:
@@ -441,6 +442,27 @@ def main():
     samples = {n: np.array([evs[s][i].elapsed_time(evs[s][i + 1]) for s in range(args.steps)])
                for i, n in enumerate(names)}                        # ms per call, one sample per step
     per_call = {n: float(np.mean(v)) for n, v in samples.items()}
+    # Kernel pass for the ROAST-MM calls: each call launched K times in a row between two events.  A
+    # call here is one launch of one kernel, so elapsed / K is that kernel's own duration -- what a
+    # kernel trace reports -- without the few microseconds an event costs on each side of a single
+    # launch.  The per-kernel roofline is taken from this figure.
+    launch_ms = {}
+    if not args.embed_only:
+        mm_launch = {"mm_fwd_l1": lambda: roast.roast_mm_fwd(d1, X, M, H1, M_bf16=Mb),
+                     "mm_fwd_l2": lambda: roast.roast_mm_fwd(d2, H1, M, Y, M_bf16=Mb),
+                     "mm_bwd_dx_l2": lambda: roast.roast_mm_bwd_dx(d2, dY, M, dH1, M_bf16=Mb),
+                     "mm_bwd_dM_l2": lambda: roast.roast_mm_bwd_dM(d2, H1, dY, dM, mode, ws),
+                     "mm_bwd_dx_l1": lambda: roast.roast_mm_bwd_dx(d1, dH1, M, dX, M_bf16=Mb),
+                     "mm_bwd_dM_l1": lambda: roast.roast_mm_bwd_dM(d1, X, dH1, dM, mode, ws)}
+        for n, fn in mm_launch.items():
+            k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            k0.record()
+            for _ in range(args.steps):
+                fn()
+            k1.record()
+            torch.cuda.synchronize()
+            launch_ms[n] = k0.elapsed_time(k1) / args.steps
     # Timed pass: exactly K steps between two synchronisations, calls back to back as a training loop
     # issues them; events only where the step passes from ROAST-MM to the lookup and from the lookup's
     # forward to its gradient, to split the step's time between the two metrics.
@@ -469,8 +491,9 @@ def main():
                                      "|M|=47185) + cfg4_dlrm_embed_f32 (1703936 lookups x 128, chunk 32, |M|=1.28M)",
                          "reduce": args.reduce, "dm_workspace": ws is not None},
               "timing": "value, mm_ms, the embedding GB/s and ms_per_step come from the timed pass (K steps, calls back to "
-                        "back, events at the two section boundaries only); per_call_* and the per-kernel rooflines come from "
-                        "an instrumented pass of the same K steps run before it (an event around every call)",
+                        "back, events at the two section boundaries only); per_call_* come from an instrumented pass of the "
+                        "same K steps run before it (an event around every call); kernel_ms and the ROAST-MM per-kernel "
+                        "rooflines from a kernel pass (each call K times in a row between two events)",
               "section_ms": {"roast_mm (shadow + 6 calls)": sec_ms[0], "embed_fwd": sec_ms[1], "embed_bwd": sec_ms[2]},
               "per_call_ms": per_call,
               "per_call_median_ms": {n: float(np.median(v)) for n, v in samples.items()},
@@ -493,26 +516,29 @@ def main():
         result["pct_mfma_peak"] = 100.0 * tflops / PEAK_BF16_TFLOPS
         # Per-call rooflines.  A forward / dX / dM call in this configuration (bf16 shadow, atomic dM
         # without workspace) is exactly one launch of one instantiation of the MFMA kernel template,
-        # so the call's HIP-event time on the launch stream is that kernel's duration.
+        # so the kernel pass's time per launch on the launch stream is that kernel's duration.
         mm_calls = [k for k in per_call if k.startswith("mm_")]
         result["roofline_per_call"] = {
-            k: {"achieved": flop_layer[k[-2:]] / (per_call[k] * 1e-3) / 1e12, "unit": "TFLOP/s",
-                "frac": flop_layer[k[-2:]] / (per_call[k] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS} for k in mm_calls}
+            k: {"achieved": flop_layer[k[-2:]] / (launch_ms[k] * 1e-3) / 1e12, "unit": "TFLOP/s",
+                "frac": flop_layer[k[-2:]] / (launch_ms[k] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                "launch_us": 1e3 * launch_ms[k], "call_us_instrumented": 1e3 * per_call[k]} for k in mm_calls}
         # The dominant kernel = the instantiation with the largest total time per step: the dM
         # product (MODE 2, two launches per step, one per layer; both 38.65 GFLOP).
         by_kind = {"k_roast_mfma<MODE_DM> (mm_bwd_dM_l1 + mm_bwd_dM_l2)": ["mm_bwd_dM_l1", "mm_bwd_dM_l2"],
                    "k_roast_mfma<MODE_FWD> (mm_fwd_l1 + mm_fwd_l2)": ["mm_fwd_l1", "mm_fwd_l2"],
                    "k_roast_mfma<MODE_DX> (mm_bwd_dx_l1 + mm_bwd_dx_l2)": ["mm_bwd_dx_l1", "mm_bwd_dx_l2"]}
-        dom = max(by_kind, key=lambda k: sum(per_call[c] for c in by_kind[k]))
+        dom = max(by_kind, key=lambda k: sum(launch_ms[c] for c in by_kind[k]))
         calls = by_kind[dom]
-        ach = sum(flop_layer[c[-2:]] for c in calls) / (sum(per_call[c] for c in calls) * 1e-3) / 1e12
+        ach = sum(flop_layer[c[-2:]] for c in calls) / (sum(launch_ms[c] for c in calls) * 1e-3) / 1e12
         traffic = None
         if args.reduce == "atomic" and ws is None:       # the configuration the committed summary was taken in
             traffic = traffic_of(load_measured_traffic(), calls, "k_roast_mfma") / len(calls)
         result["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                               "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic,
                               "launches_per_step": len(calls),
-                              "avg_launch_us": 1e3 * sum(per_call[c] for c in calls) / len(calls)}
+                              "avg_launch_us": 1e3 * sum(launch_ms[c] for c in calls) / len(calls),
+                              "avg_call_us_instrumented": 1e3 * sum(per_call[c] for c in calls) / len(calls)}
+        result["kernel_ms"] = launch_ms
     if not args.mm_only:
         # compulsory HBM bytes: output (or dOut) once, ids once, M (and dM read+write) once
         ids = N * (8 + 4)

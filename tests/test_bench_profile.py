@@ -43,3 +43,22 @@ def test_missing_or_malformed_summary_is_an_error(tmp_path):
         bench.traffic_of(rows, ["embed_fwd"], "k_embed")
     with pytest.raises(OSError):
         bench.load_measured_traffic(str(tmp_path / "absent.txt"))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("flags", [["--mm-only"], ["--embed-only"], ["--reduce", "deterministic"]])
+def test_profiling_runs_of_the_bench_print_a_line(flags):
+    """The flag combinations the committed rocprofv3 summaries were collected with must run to the end
+    and print one JSON line with the fields the summaries quote."""
+    import json
+    import subprocess
+    cmd = [sys.executable, os.path.join(ROOT, "bench.py"), "--no-cpu-baseline", "--hot-path-only",
+           "--steps", "2", "--warmup", "1"] + flags
+    r = subprocess.run(cmd, cwd=ROOT, capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0, r.stderr[-2000:]
+    line = json.loads(r.stdout.strip().splitlines()[-1])
+    assert line["steps"] == 2 and line["ms_per_step"] > 0
+    if "--embed-only" not in flags:
+        assert line["roofline"]["avg_launch_us"] > 0 and set(line["kernel_ms"]) == set(line["roofline_per_call"])
+    if "--mm-only" not in flags:
+        assert line["embedding"]["value"] > 0
