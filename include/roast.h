@@ -214,6 +214,17 @@ roast_status roast_mm_bwd_dx_ws(const roast_mm_desc* d, roast_dtype dt, int64_t 
                                 const float* M, const void* M_bf16, void* dX, int64_t ldx, void* workspace,
                                 size_t workspace_bytes, void* stream);
 
+/*
+ * Diagnostic, host only, launches nothing: how many consecutive 128-column output blocks one
+ * workgroup of the bf16 matrix-core kernels computes, one after the other as a single run of
+ * contraction steps, in roast_mm_fwd (which = 0) or roast_mm_bwd_dx (which = 1) on I rows with a
+ * bf16 shadow and no workspace.  This is Algorithm 1's loop order seen from one workgroup: a fixed
+ * row block i, the column blocks j of its strip in turn, the contraction k innermost.  1 = one block
+ * per workgroup (also for shapes that take other kernels); 0 = invalid descriptor, I or `which`.
+ * For tests (which must know that a shape exercises the strip path) and for tuning.
+ */
+int roast_mm_strip_blocks(const roast_mm_desc* d, int64_t I, int which);
+
 /* Bytes of workspace roast_mm_bwd_dM can use for these sizes and mode (0 = none).
  * DETERMINISTIC: required.  ATOMIC: optional -- with it (bf16 path, contraction split over several
  * workgroups) the per-split products are summed in the workspace and scattered with one atomic per

@@ -21,7 +21,7 @@ EXPORTS = ["roast_status_string", "roast_tile_index", "roast_tile_index_device",
            "roast_m_shadow_bytes", "roast_m_shadow_bf16", "roast_m_planes_bytes", "roast_m_planes_bf16",
            "roast_mm_fwd", "roast_mm_bwd_dx",
            "roast_mm_fwd_workspace", "roast_mm_bwd_dx_workspace", "roast_mm_fwd_ws", "roast_mm_bwd_dx_ws",
-           "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_mm_bwd_dM",
+           "roast_mm_strip_blocks", "roast_mm_bwd_dM_workspace", "roast_mm_bwd_dM_workspace_f32", "roast_mm_bwd_dM",
            "roast_embed_fwd", "roast_embed_bwd_workspace", "roast_embed_bwd", "roast_embed_bwd_noalloc",
            "roast_embed_bag_fwd", "roast_embed_bag_bwd_workspace", "roast_embed_bag_bwd", "roast_optim_step"]
 
@@ -95,6 +95,7 @@ def load() -> C.CDLL:
         getattr(lib, name).argtypes = [MP, i32, i64]
         getattr(lib, name).restype = sz
     lib.roast_mm_fwd_ws.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
+    lib.roast_mm_strip_blocks.argtypes = [MP, i64, i32]
     lib.roast_mm_bwd_dx_ws.argtypes = [MP, i32, i64, vp, i64, vp, vp, vp, i64, vp, sz, vp]
     lib.roast_mm_bwd_dM_workspace.argtypes = [MP, i64, i32]
     lib.roast_mm_bwd_dM_workspace.restype = sz
@@ -271,6 +272,11 @@ def roast_mm_bwd_dx_workspace(desc: RoastMMDesc, dtype, I: int) -> int:
     torch = _torch()
     code = {torch.float32: ROAST_F32, torch.bfloat16: ROAST_BF16}[dtype]
     return int(load().roast_mm_bwd_dx_workspace(C.byref(desc), code, int(I)))
+
+
+def roast_mm_strip_blocks(desc: RoastMMDesc, I: int, which: int) -> int:
+    """Consecutive column blocks per workgroup in roast_mm_fwd (which = 0) / roast_mm_bwd_dx (which = 1)."""
+    return int(load().roast_mm_strip_blocks(C.byref(desc), int(I), int(which)))
 
 
 def roast_mm_fwd(desc: RoastMMDesc, X, M, Y=None, stream=None, M_bf16=None, ws=None):

@@ -145,6 +145,12 @@ size_t roast_mm_bwd_dx_workspace(const roast_mm_desc* d, roast_dtype dt, int64_t
   return s > 1 ? (size_t)s * (size_t)I * (size_t)a.H * sizeof(float) : 0;
 }
 
+int roast_mm_strip_blocks(const roast_mm_desc* d, int64_t I, int which) {
+  MMArgs a;
+  if (make_mm_args(d, I, &a) != ROAST_OK || I <= 0 || (which != 0 && which != 1)) return 0;
+  return which == 0 ? mfma_fwd_strip(a, true) : mfma_dx_strip(a, true);
+}
+
 roast_status roast_mm_fwd_ws(const roast_mm_desc* d, roast_dtype dt, int64_t I, const void* X, int64_t ldx,
                              const float* M, const void* M_bf16, void* Y, int64_t ldy, void* workspace,
                              size_t workspace_bytes, void* stream) {

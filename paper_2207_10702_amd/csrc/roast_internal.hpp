@@ -111,6 +111,8 @@ roast_status shadow_bf16_launch(const float* M, int64_t m_size, void* shadow, hi
 // ws (optional): room for mfma_*_splits() fp32 partial outputs [parts][I][columns]; when given and the
 // shape has too few output tiles to fill the chip, the contraction axis is split over workgroups.
 int mfma_fwd_splits(const MMArgs& a);    // 1: no split (or shape not handled by these kernels)
+int mfma_fwd_strip(const MMArgs& a, bool shadow);   // consecutive column blocks per workgroup (1: none) when the contraction is not split
+int mfma_dx_strip(const MMArgs& a, bool shadow);
 int mfma_dx_splits(const MMArgs& a);
 roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const float* M, const void* M_bf16, void* Y,
                          int64_t ldy, float* ws, hipStream_t s);

@@ -32,6 +32,12 @@
 // forward / dX goes through LDS (the operand stages, free by then) so that global stores are 16
 // bytes per lane and row-contiguous.  Workgroups are numbered so that each XCD's L2 serves a
 // contiguous band of output row blocks.
+// Strips: where a launch has more blocks than CUs and few steps per block, a forward / dX workgroup
+// computes several consecutive column blocks of its row block as one unbroken sequence of steps
+// (Algorithm 1's loop nest seen from one workgroup: row block fixed, column blocks in turn,
+// contraction innermost).  The producers never drain between blocks, the tile table is built once,
+// and an inner block's accumulators leave through a small private staging area while the first
+// stages of the next block are already in LDS.
 #include <atomic>
 #include <type_traits>
 #include <utility>
@@ -66,6 +72,7 @@ constexpr int BK = 64;
 constexpr int kBM = 256, kBN = 128;   // workgroup tile of every kernel here ...
 constexpr int kBNarrow = 96;          // ... but the narrow forward / dX blocks
 constexpr int kMaxTable = 2048; // tile-table entries a workgroup may need
+constexpr int kStripTable = 768; // ... when it computes a strip of blocks: the table's tail then stages the strip's inner blocks
 enum { MODE_FWD = 0, MODE_DX = 1, MODE_DM = 2 };
 
 __device__ inline uint32_t pack_bf16x2(float a, float b) {
@@ -104,6 +111,10 @@ struct KernArgs {
   int rows_per_split;  // length of one part of the contraction axis (DM always; FWD / DX when nbz > 1)
   int split_begin[18]; // dM with uneven parts (all zero: unused): part z covers rows [split_begin[z], split_begin[z+1])
   int nbx, nby, nbz;   // logical block grid: columns (x), rows (y), contraction splits (z)
+  // Forward / dX strips: a workgroup computes `ntile` consecutive column blocks one after the other
+  // as one continuous sequence of contraction steps (1 = one block per workgroup); consecutive
+  // blocks of a strip are `tile_shift` = BN / Z hash tiles apart.
+  int ntile, tile_shift;
 };
 
 // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Blocks that share
@@ -282,7 +293,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
   const int I = (int)a.I;
   int bx, by, bz;
   if (!block_coords(p, &bx, &by, &bz)) return;   // whole workgroup leaves before any barrier
-  const int m0 = by * BM, n0 = bx * BN;
+  const int NTL = MODE == MODE_DM ? 1 : max(p.ntile, 1);     // column blocks of this workgroup's strip
+  const int m0 = by * BM, n0 = bx * BN * NTL;                // n0: first column of the strip
   const int Mdim = MODE == MODE_DM ? (int)a.H : I;
   const int Ndim = MODE == MODE_DX ? (int)a.H : (int)a.O;
   int k_begin = 0, k_end = MODE == MODE_FWD ? (int)a.H : (MODE == MODE_DX ? (int)a.O : I);
@@ -296,8 +308,12 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     }
   }
   const int nsteps_k = max(0, (k_end - k_begin + BK - 1) / BK);
-  const int nsteps = X3 ? 6 * nsteps_k : nsteps_k;               // identical for every wave of the workgroup
-  auto step_k0 = [&](int step) { return k_begin + (X3 ? step / 6 : step) * BK; };
+  // A strip runs its blocks back to back: step s belongs to block s / nsteps_k and to contraction
+  // step s % nsteps_k of it, so the producers never drain between two blocks of a strip.
+  const int nsteps = X3 ? 6 * nsteps_k : nsteps_k * NTL;         // identical for every wave of the workgroup
+  const int nk1 = max(nsteps_k, 1);
+  auto step_k0 = [&](int step) { return k_begin + (X3 ? step / 6 : (NTL == 1 ? step : step % nk1)) * BK; };
+  auto step_shift = [&](int step) { return NTL == 1 ? 0 : (step / nk1) * p.tile_shift; };   // hash tiles between block 0 and the step's block
   auto step_asel = [&](int step) { return X3 ? (0x120100 >> (4 * (step % 6))) & 3 : 0; };   // plane of A
   auto step_bsel = [&](int step) { return X3 ? (0x102010 >> (4 * (step % 6))) & 3 : 0; };   // plane of B / M
 
@@ -312,11 +328,11 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
     int x0 = 0, y0 = 0, cnt = 0;
     if (MODE == MODE_FWD) {
       y0 = n0 / a.Z2;
-      TN = (min(n0 + BN, (int)a.O) - 1) / a.Z2 - y0 + 1;
+      TN = (min(n0 + BN * NTL, (int)a.O) - 1) / a.Z2 - y0 + 1;
       cnt = (int)a.nTx * TN;
     } else if (MODE == MODE_DX) {
       x0 = n0 / a.Z1;
-      TN = (min(n0 + BN, (int)a.H) - 1) / a.Z1 - x0 + 1;
+      TN = (min(n0 + BN * NTL, (int)a.H) - 1) / a.Z1 - x0 + 1;
       cnt = (int)a.nTy * TN;
     } else {
       x0 = m0 / a.Z1; y0 = n0 / a.Z2;
@@ -484,7 +500,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         // they repeat the last row block's loads and store nothing)
         const int kraw = k0 + 4 * min(pt / Ctx::FS_NG, 15);
         const int kabs = RAGK ? min(kraw, k_end - 4) : kraw;   // rows beyond a ragged contraction length: zeros below
-        const int e = (kabs / a.Z1) * TN + c.fs_yl;
+        const int e = (kabs / a.Z1) * TN + c.fs_yl + step_shift(step);
         const int64_t off0 = s_off[e];
         const int64_t rel = off0 + (int64_t)a.Z2 * (kabs % a.Z1) + c.fs_nin;
         // everything added to the tile base is even (Z2 % 8 == 0): the base's parity picks the copy
@@ -499,7 +515,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         static_assert(MODE != MODE_FWD || SHADOW || Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
         const int kraw = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
-        const int e = (kabs / a.Z1) * TN + c.fw_yl;
+        const int e = (kabs / a.Z1) * TN + c.fw_yl + step_shift(step);
         const int64_t rel = s_off[e] + (int64_t)a.Z2 * (kabs % a.Z1) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
 #pragma unroll
@@ -514,7 +530,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         // this thread's 8-wide chunk of the contraction axis lies in one hash tile (Z2 % 8 == 0)
         const int kraw = k0 + 8 * (pt & 7);
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;   // chunks beyond a ragged contraction length: zeros
-        const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
+        const int kt = (kabs / a.Z2) * TN + step_shift(step), kin = kabs % a.Z2;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
@@ -527,7 +543,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       } else if (MODE == MODE_DX) {
         const int kraw = k0 + 8 * (pt & 7);
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
-        const int kt = (kabs / a.Z2) * TN, kin = kabs % a.Z2;
+        const int kt = (kabs / a.Z2) * TN + step_shift(step), kin = kabs % a.Z2;
         const float keep = (!RAGK || kraw < k_end) ? 1.f : 0.f;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
@@ -746,6 +762,43 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
 #pragma unroll
     for (int j = 0; j < NI; ++j) bfr[buf][j] = bfrag(Bt, j, ks);
   };
+  // A block of a strip that is not its last cannot be staged through the operand stages (they are
+  // busy with the next block), and storing the accumulators as they lie -- 8 bytes per lane, 32 rows
+  // per instruction -- costs as much as a workgroup's whole fixed cost (measured: 4 us per block on
+  // the BERT-FFN forward).  A strip's tile table is short (the host sees to it), so the unused tail of
+  // the offset table serves as a small staging area: each wave passes its tile through its own
+  // 8 rows x 128 bytes, eight rows at a time, and stores them 16 bytes per lane, row-contiguous.
+  // The same wave writes and reads: LDS operations of one wave complete in order.
+  constexpr int kStripStageRows = 8;
+  static_assert(WTN != 64 || kStripTable * 8 + NC * kStripStageRows * EPI_STRIDE <= kMaxTable * 8,
+                "a strip's tile table and its staging rows share the offset table's space");
+  [[maybe_unused]] auto store_block_staged = [&](int t) {
+    if constexpr (WTN == 64) {
+      char* ebuf = reinterpret_cast<char*>(s_off) + kMaxTable * 8 - (NC - wave) * (kStripStageRows * EPI_STRIDE);
+      const int cb = n0 + t * BN + wn * WTN;
+      const int lr = lane & 31;
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int r8 = 0; r8 < 32 / kStripStageRows; ++r8) {
+          if ((lr >> 3) == r8) {
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const uint2v w = {pack_bf16x2(a.lambda * acc[i][j][4 * q], a.lambda * acc[i][j][4 * q + 1]),
+                                  pack_bf16x2(a.lambda * acc[i][j][4 * q + 2], a.lambda * acc[i][j][4 * q + 3])};
+                *reinterpret_cast<uint2v*>(ebuf + (lr & 7) * EPI_STRIDE + (j * 32 + 8 * q + 4 * (lane >> 5)) * 2) = w;
+              }
+          }
+          const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + (lane >> 3) * EPI_STRIDE + (lane & 7) * 16);
+          const int row = m0 + wm * WTM + i * 32 + r8 * kStripStageRows + (lane >> 3);
+          if (row < Mdim)
+            __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + cb + (lane & 7) * 8));
+        }
+    }
+  };
+  int blk = 0, k_in_blk = 0;                             // strip: current block and steps done in it
   if (nsteps > 0) {
     __syncthreads();                                     // barrier 0: stages hold step 0
     fetch(0, 0, 0);
@@ -774,8 +827,24 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         }
       __builtin_amdgcn_sched_barrier(0);
     }
+    if constexpr (MODE != MODE_DM && !X3 && !ELEM && WTN == 64) {
+      if (NTL > 1 && ++k_in_blk == nsteps_k && s + 1 < nsteps) {
+        // a block of the strip is complete and another follows (its first fragments are already in
+        // registers): store it and start over
+        store_block_staged(blk);
+        ++blk;
+        k_in_blk = 0;
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      }
+    }
   }
-  // ---- epilogue (consumer waves only)
+  // ---- epilogue (consumer waves only): the last (or only) block of the strip
+  const int n0e = n0 + (NTL - 1) * BN;
   if (MODE != MODE_DM) {
     __syncthreads();   // every wave is done with the operand stages: they become the staging buffers
     // acc[i][j][e]: output row = i*32 + (lane & 31), column = j*32 + 8*(e/4) + 4*(lane >> 5) + e%4.
@@ -805,7 +874,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
           const int r = it * RPI + lane / CPR, cc = lane % CPR;
           if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;   // (only when CPR does not divide 64)
           const float4v v = *reinterpret_cast<const float4v*>(ebuf + r * ES + cc * 16);
-          const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 4;
+          const int row = m0 + wm * WTM + i * 32 + r, col = n0e + wn * WTN + cc * 4;
           if (row < Mdim && col < Ndim) {
             // partial tiles are read again by the finishing kernel; a final result is not
             if (p.G) *reinterpret_cast<float4v*>(part + row * ldp + col) = v;
@@ -834,7 +903,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         const int r = it * RPI + lane / CPR, cc = lane % CPR;
         if ((64 % CPR != 0) && (lane / CPR >= RPI || r >= 32)) continue;     // (only when CPR does not divide 64)
         const uint4v v = *reinterpret_cast<const uint4v*>(ebuf + r * EPI_STRIDE + cc * 16);
-        const int row = m0 + wm * WTM + i * 32 + r, col = n0 + wn * WTN + cc * 8;
+        const int row = m0 + wm * WTM + i * 32 + r, col = n0e + wn * WTN + cc * 8;
         if (row < Mdim && col < Ndim) __builtin_nontemporal_store(v, reinterpret_cast<uint4v*>(p.C + (int64_t)row * p.ldc + col));
       }
     }
@@ -1052,6 +1121,30 @@ inline bool narrow_pays(int64_t rb, int64_t n) {
   return cdiv(rb * cdiv(n, kBNarrow), 256) * kBNarrow < cdiv(rb * cdiv(n, kBN), 256) * kBN;
 }
 
+// Column blocks per workgroup strip for a forward / dX launch with rb row blocks, n output columns,
+// hash tiles of z columns, `steps` contraction steps per block and tiles_k hash tiles along the
+// contraction.  Model (microseconds, fitted to the BERT-FFN and BERT-QKV shapes): a step takes 1.2,
+// a workgroup 3.3 of fixed cost (launch, tile table, first loads, the staged epilogue and its drain),
+// a further block of a strip 0.9 (its stores through the small staging area); workgroups beyond 256
+// queue, a last partial round counting half.  Strips need whole blocks of whole hash tiles
+// (n % (kBN * t) == 0, kBN % z == 0) and a tile table short enough to leave the staging rows free;
+// the candidate with the smallest modelled time wins, so strips form where short blocks would
+// otherwise queue for the CUs (8192 x 768 -> 3072: three rounds of 12-step blocks become one round
+// of 36-step strips, 58 -> 53 us) and not where they would leave CUs idle.
+inline int pick_ntile(int64_t rb, int64_t n, int64_t z, int64_t steps, int64_t tiles_k) {
+  if (z <= 0 || kBN % z != 0) return 1;
+  int best = 1;
+  double best_cost = 0.0;
+  for (int t = 1; t <= 4; ++t) {
+    if (n % ((int64_t)kBN * t) != 0 || tiles_k * ((int64_t)kBN * t / z) > (t == 1 ? kMaxTable : kStripTable)) continue;
+    const double wgs = (double)(rb * (n / ((int64_t)kBN * t)));
+    const double rounds = wgs <= 256.0 ? 1.0 : 0.5 * ((double)cdiv((int64_t)wgs, 256) + wgs / 256.0);
+    const double cost = rounds * ((double)(t * steps) * 1.2 + 3.3 + 0.9 * (t - 1));
+    if (t == 1 || cost < best_cost) { best_cost = cost; best = t; }
+  }
+  return best;
+}
+
 }  // namespace
 
 
@@ -1131,6 +1224,19 @@ bool mfma_elem_ok(const MMArgs& a) { return a.H % 8 == 0 && a.O % 8 == 0; }
 
 }  // namespace
 
+// Blocks per strip of a forward / dX launch whose contraction is not split (1 wherever the launch
+// takes another instantiation: element-wise, ragged contraction, narrow blocks).
+int mfma_fwd_strip(const MMArgs& a, bool shadow) {
+  if (!mfma_fwd_ok(a) || a.H % BK != 0) return 1;
+  if (shadow && a.Z2 % 8 == 0 && narrow_pays(cdiv(a.I, kBM), a.O)) return 1;
+  return pick_ntile(cdiv(a.I, kBM), a.O, a.Z2, a.H / BK, a.nTx);
+}
+int mfma_dx_strip(const MMArgs& a, bool shadow) {
+  if (!mfma_dx_ok(a) || a.O % BK != 0) return 1;
+  if (shadow && narrow_pays(cdiv(a.I, kBM), a.H)) return 1;
+  return pick_ntile(cdiv(a.I, kBM), a.H, a.Z1, a.O / BK, a.nTy);
+}
+
 int mfma_fwd_splits(const MMArgs& a) {
   return (mfma_fwd_ok(a) || mfma_elem_ok(a)) ? mm_pick_splits(cdiv(a.O, kBN) * cdiv(a.I, kBM), a.H) : 1;
 }
@@ -1162,8 +1268,14 @@ roast_status mfma_mm_fwd(const MMArgs& a, const void* X, int64_t ldx, const floa
   } else if (a.H % BK != 0)
     st = shadow ? launch<MODE_FWD, BM, BN, 4, 2, true, false, true>(p, grid, s)
                 : launch<MODE_FWD, BM, BN, 4, 2, false, false, true>(p, grid, s);
-  else
+  else {
+    if (grid.z == 1) {
+      p.ntile = mfma_fwd_strip(a, shadow);
+      p.tile_shift = BN / a.Z2;
+      grid.x = (unsigned)cdiv(a.O, (int64_t)BN * p.ntile);
+    }
     st = shadow ? launch<MODE_FWD, BM, BN, 4, 2, true>(p, grid, s) : launch<MODE_FWD, BM, BN, 4, 2, false>(p, grid, s);
+  }
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.O, s);
 }
 
@@ -1188,8 +1300,14 @@ roast_status mfma_mm_bwd_dx(const MMArgs& a, const void* dY, int64_t ldy, const 
   } else if (a.O % BK != 0)
     st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true, false, true>(p, grid, s)
                 : launch<MODE_DX, BM, BN, 4, 2, false, false, true>(p, grid, s);
-  else
+  else {
+    if (grid.z == 1) {
+      p.ntile = mfma_dx_strip(a, M_bf16 != nullptr);
+      p.tile_shift = BN / a.Z1;
+      grid.x = (unsigned)cdiv(a.H, (int64_t)BN * p.ntile);
+    }
     st = M_bf16 ? launch<MODE_DX, BM, BN, 4, 2, true>(p, grid, s) : launch<MODE_DX, BM, BN, 4, 2, false>(p, grid, s);
+  }
   return st != ROAST_OK ? st : split_finish(p, grid.z, a.I, a.H, s);
 }
 

@@ -100,3 +100,15 @@ def test_optim_step_argument_validation():
     assert lib.roast_optim_step(C.byref(d), 0, None, None, None, None, None, None) == 0  # empty: no-op
     d = roast.optim_desc(roast.ROAST_OPT_ADAGRAD, 1e-3)
     assert lib.roast_optim_step(C.byref(d), 16, 16, 16, None, None, None, None) == 1     # state1 missing
+
+
+def test_strip_diagnostic_on_config_shapes_and_bad_arguments():
+    roast = binding
+    h = wl.draw_hash(np.random.default_rng(1), use_sign=True, align=1)
+    d = roast.mm_desc(768, 3072, 64, 64, 47185, 1, np.float32(1.0), h)
+    assert roast.roast_mm_strip_blocks(d, 8192, 0) == 3       # the BERT-FFN forward: 768 blocks -> 256 strips
+    assert roast.roast_mm_strip_blocks(d, 8192, 1) == 1       # its dX has 768-wide outputs: narrow blocks instead
+    assert roast.roast_mm_strip_blocks(d, 256, 0) == 1        # 24 blocks: nothing queues
+    assert roast.roast_mm_strip_blocks(d, 0, 0) == 0 and roast.roast_mm_strip_blocks(d, 8192, 2) == 0
+    bad = roast.mm_desc(768, 3072, 64, 64, 100, 1, np.float32(1.0), h)   # |M| smaller than a tile
+    assert roast.roast_mm_strip_blocks(bad, 8192, 0) == 0
