@@ -21,7 +21,7 @@
 //            4(n) register blocks, signed, rounded to bf16 and written per column (two stages);
 //   dX:      dY rows likewise straight to LDS; the tile's rows run along O = the contraction, so it
 //            is signed, rounded and copied row by row through registers;
-//   dM:      contraction is over token rows, so X and dY are both transposed as 8 x 8 (8 x 4) bf16
+//   dM:      contraction is over token rows, so X and dY are both transposed as 8 x 8 (4 x 8) bf16
 //            blocks with v_perm_b32 on their way through registers (two stages each).
 // Register loads run several steps ahead (one register set per step in flight); the wait counters
 // are in-order, so the producer loop is branch-free and keeps one issue order, and its barriers are
@@ -134,27 +134,24 @@ __device__ inline bool block_coords(const KernArgs& p, int* bx, int* by, int* bz
   return true;
 }
 
-// Transposing loader for a bf16 [BK rows (k)][W cols] tile whose rows are contiguous in memory:
-// each thread owns an 8(k) x CW(cols) block (CW = W/32), loads its 8 row pieces, and writes CW
-// 16-byte chunks (8 k-values of one column) to the [col][k] LDS tile.
+// Transposing loaders for a bf16 [BK rows (k)][W cols] tile whose rows are contiguous in memory, one
+// per tile width, both with 16-byte loads (a wave's vector-memory instructions issue slowly next to
+// busy consumers, so a step's bytes should come in as few of them as possible: with 8-byte loads for
+// the 128-wide tile the dM product took 3-5 % longer).
+// 256 columns: each thread owns an 8(k) x 8(cols) block, loads its 8 row pieces, and writes 8 16-byte
+// chunks (8 k-values of one column) to the [col][k] LDS tile.
 template <int W>
 struct TLoad {
-  static constexpr int CW = W / 32;             // columns per thread: 8 (16-byte loads) or 4 (8-byte loads)
-  static constexpr int DW = CW / 2;             // dwords per row piece
-  static_assert(CW == 8 || CW == 4, "tile width must be 256 or 128");
-  uint32_t r[8][DW];
+  static_assert(W == 256, "the 128-column tile has its own loader");
+  static constexpr int KB_SHIFT = 5, COL_MASK = 31;   // thread -> column block ptid & 31 (8 columns), k-block ptid >> 5 (8 rows)
+  static constexpr int COLS = 8;                      // columns per thread
+  uint32_t r[8][4];
   __device__ void load(const uint16_t* src, int64_t ld, int k0, int kmax_row, int col, int kb) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
       const int row = min(k0 + 8 * kb + q, kmax_row);
-      const uint16_t* p = src + (int64_t)row * ld + col;
-      if constexpr (DW == 4) {
-        uint4v v = *reinterpret_cast<const uint4v*>(p);
-        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
-      } else {
-        uint2v v = *reinterpret_cast<const uint2v*>(p);
-        r[q][0] = v[0]; r[q][1] = v[1];
-      }
+      const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
+      r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
     }
   }
   // rows at or beyond k_end are zeroed (they would add into sums that are kept)
@@ -163,15 +160,46 @@ struct TLoad {
     for (int q = 0; q < 8; ++q)
       if (k0 + 8 * kb + q >= k_end) {
 #pragma unroll
-        for (int d = 0; d < DW; ++d) r[q][d] = 0u;
+        for (int d = 0; d < 4; ++d) r[q][d] = 0u;
       }
 #pragma unroll
-    for (int c = 0; c < CW; ++c) {
+    for (int c = 0; c < 8; ++c) {
       const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
       uint4v o;
 #pragma unroll
       for (int pr = 0; pr < 4; ++pr) o[pr] = __builtin_amdgcn_perm(r[2 * pr + 1][c >> 1], r[2 * pr][c >> 1], sel);
-      *reinterpret_cast<uint4v*>(tile + lds_off(colblk * CW + c, kb)) = o;
+      *reinterpret_cast<uint4v*>(tile + lds_off(colblk * 8 + c, kb)) = o;
+    }
+  }
+};
+// 128 columns: each thread owns a 4(k) x 8(cols) block, loads its 4 row pieces, and writes 8 half
+// chunks (4 k-values of one column, 8 bytes).
+template <>
+struct TLoad<128> {
+  static constexpr int KB_SHIFT = 4, COL_MASK = 15;   // thread -> column group ptid & 15 (8 columns), k-block ptid >> 4 (4 rows)
+  static constexpr int COLS = 8;
+  uint32_t r[4][4];
+  __device__ void load(const uint16_t* src, int64_t ld, int k0, int kmax_row, int col, int kb) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = min(k0 + 4 * kb + q, kmax_row);
+      const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
+      r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+    }
+  }
+  __device__ void store(char* tile, int k0, int k_end, int colblk, int kb) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (k0 + 4 * kb + q >= k_end) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) r[q][d] = 0u;
+      }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+      const uint2v o = {__builtin_amdgcn_perm(r[1][c >> 1], r[0][c >> 1], sel),
+                        __builtin_amdgcn_perm(r[3][c >> 1], r[2][c >> 1], sel)};
+      *reinterpret_cast<uint2v*>(tile + lds_off(colblk * 8 + c, kb >> 1) + 8 * (kb & 1)) = o;
     }
   }
 };
@@ -195,7 +223,7 @@ struct ProdCtx {
   // DX, B operand: BN rows (h) x 8 chunks of 8 floats; thread -> chunk (ptid & 7) of rows (ptid >> 3) + 32*q
   int dx_ent[MODE == MODE_DX ? DX_LOADS : 1];
   int dx_rowoff[MODE == MODE_DX ? DX_LOADS : 1];
-  // DM: 8(k) x CW blocks of both operands; thread -> column block ptid & 31, k-block ptid >> 5
+  // DM: 8(k) x 8 blocks of X, 4(k) x 8 blocks of dY (TLoad<256>, TLoad<128>): first column of this thread's block
   int ta_col, tb_col;
   // ELEM (forward / dX, one hash per virtual weight): thread -> LDS row ptid & 127 (one output
   // column: the "fixed" coordinate) and half ptid >> 7 of the 64-deep step (32 consecutive values of
@@ -419,9 +447,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         c.dx_rowoff[q] = a.Z2 * (h % a.Z1);
       }
     }
-    if (MODE == MODE_DM) {
-      c.ta_col = min(m0 + (pt & 31) * (BM / 32), (int)a.H - BM / 32);
-      c.tb_col = min(n0 + (pt & 31) * (BN / 32), (int)a.O - BN / 32);
+    if constexpr (MODE == MODE_DM) {
+      c.ta_col = min(m0 + (pt & TLoad<BM>::COL_MASK) * TLoad<BM>::COLS, (int)a.H - TLoad<BM>::COLS);
+      c.tb_col = min(n0 + (pt & TLoad<BN>::COL_MASK) * TLoad<BN>::COLS, (int)a.O - TLoad<BN>::COLS);
     }
     // ELEM.  W[i, j] sits at offset(x, y) + Z2 * (i mod Z1) + (j mod Z2), x = i / Z1, y = j / Z2, with
     // sign g(x, y) or g(i, j).  The hash of a key is a sum of per-coordinate terms mod P, so a thread
@@ -624,10 +652,10 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         const int64_t plane = is_a ? p.a_plane : p.b_plane;
         auto fetch = [&](TL& r, int step) {
           const uint16_t* from = X3 ? src + (is_a ? step_asel(step) : step_bsel(step)) * plane : src;
-          r.load(from, ld, step_k0(step), I - 1, col, pt >> 5);
+          r.load(from, ld, step_k0(step), I - 1, col, pt >> TL::KB_SHIFT);
         };
         auto stage = [&](TL& r, int step) {
-          r.store(is_a ? a_stage(step) : b_stage(step), step_k0(step), k_end, pt & 31, pt >> 5);
+          r.store(is_a ? a_stage(step) : b_stage(step), step_k0(step), k_end, pt & TL::COL_MASK, pt >> TL::KB_SHIFT);
         };
         const int last = nsteps - 1;
         if (nsteps > 0) {
