@@ -115,7 +115,21 @@ struct KernArgs {
   // as one continuous sequence of contraction steps (1 = one block per workgroup); consecutive
   // blocks of a strip are `tile_shift` = BN / Z hash tiles apart.
   int ntile, tile_shift;
+  // log2 of Z1 / Z2 when they are powers of two, else -1 (set by launch()): the per-step tile lookups
+  // of the load waves and the dM epilogue then shift and mask instead of dividing
+  int z1_shift, z2_shift;
 };
+
+// v / z and v % z for v >= 0: a shift and a mask when z is a power of two (sh = log2 z), the division
+// otherwise.  sh is uniform, so this is a scalar branch around ~25 instructions per division.
+__device__ inline int tile_div(int v, int z, int sh) {
+  if (sh >= 0) return v >> sh;
+  return v / z;
+}
+__device__ inline int tile_mod(int v, int z, int sh) {
+  if (sh >= 0) return v & (z - 1);
+  return v % z;
+}
 
 // Workgroups are handed to the 8 XCDs round-robin, and each XCD has its own L2.  Blocks that share
 // an operand slab (same row block -> same rows of X / dY) should therefore run on the same XCD:
@@ -147,21 +161,35 @@ struct TLoad {
   static constexpr int COLS = 8;                      // columns per thread
   uint32_t r[8][4];
   __device__ void load(const uint16_t* src, int64_t ld, int k0, int kmax_row, int col, int kb) {
+    // (both paths issue the same eight loads in the same order; the branch is uniform: only a
+    // step that reaches past the last row has to clamp its row numbers)
+    if (k0 + BK - 1 <= kmax_row) {
+      const uint16_t* p0 = src + (int64_t)(k0 + 8 * kb) * ld + col;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int row = min(k0 + 8 * kb + q, kmax_row);
-      const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
-      r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      for (int q = 0; q < 8; ++q) {
+        const uint4v v = *reinterpret_cast<const uint4v*>(p0 + (int64_t)q * ld);
+        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const int row = min(k0 + 8 * kb + q, kmax_row);
+        const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
+        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      }
     }
   }
-  // rows at or beyond k_end are zeroed (they would add into sums that are kept)
+  // rows at or beyond k_end are zeroed (they would add into sums that are kept); only the last step
+  // of a contraction part can have any (uniform branch)
   __device__ void store(char* tile, int k0, int k_end, int colblk, int kb) {
+    if (k0 + BK > k_end) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
-      if (k0 + 8 * kb + q >= k_end) {
+      for (int q = 0; q < 8; ++q)
+        if (k0 + 8 * kb + q >= k_end) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) r[q][d] = 0u;
-      }
+          for (int d = 0; d < 4; ++d) r[q][d] = 0u;
+        }
+    }
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
@@ -180,20 +208,31 @@ struct TLoad<128> {
   static constexpr int COLS = 8;
   uint32_t r[4][4];
   __device__ void load(const uint16_t* src, int64_t ld, int k0, int kmax_row, int col, int kb) {
+    if (k0 + BK - 1 <= kmax_row) {
+      const uint16_t* p0 = src + (int64_t)(k0 + 4 * kb) * ld + col;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int row = min(k0 + 4 * kb + q, kmax_row);
-      const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
-      r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      for (int q = 0; q < 4; ++q) {
+        const uint4v v = *reinterpret_cast<const uint4v*>(p0 + (int64_t)q * ld);
+        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int row = min(k0 + 4 * kb + q, kmax_row);
+        const uint4v v = *reinterpret_cast<const uint4v*>(src + (int64_t)row * ld + col);
+        r[q][0] = v[0]; r[q][1] = v[1]; r[q][2] = v[2]; r[q][3] = v[3];
+      }
     }
   }
   __device__ void store(char* tile, int k0, int k_end, int colblk, int kb) {
+    if (k0 + BK > k_end) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q)
-      if (k0 + 4 * kb + q >= k_end) {
+      for (int q = 0; q < 4; ++q)
+        if (k0 + 4 * kb + q >= k_end) {
 #pragma unroll
-        for (int d = 0; d < 4; ++d) r[q][d] = 0u;
-      }
+          for (int d = 0; d < 4; ++d) r[q][d] = 0u;
+        }
+    }
 #pragma unroll
     for (int c = 0; c < 8; ++c) {
       const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
@@ -528,9 +567,9 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         // they repeat the last row block's loads and store nothing)
         const int kraw = k0 + 4 * min(pt / Ctx::FS_NG, 15);
         const int kabs = RAGK ? min(kraw, k_end - 4) : kraw;   // rows beyond a ragged contraction length: zeros below
-        const int e = (kabs / a.Z1) * TN + c.fs_yl + step_shift(step);
+        const int e = tile_div(kabs, a.Z1, p.z1_shift) * TN + c.fs_yl + step_shift(step);
         const int64_t off0 = s_off[e];
-        const int64_t rel = off0 + (int64_t)a.Z2 * (kabs % a.Z1) + c.fs_nin;
+        const int64_t rel = off0 + (int64_t)a.Z2 * tile_mod(kabs, a.Z1, p.z1_shift) + c.fs_nin;
         // everything added to the tile base is even (Z2 % 8 == 0): the base's parity picks the copy
         const uint16_t* mb = Mb + ((off0 & 1) ? p.mb_stride - 1 : 0);
         r.fw_sgn = s_sgn[e];
@@ -543,8 +582,8 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         static_assert(MODE != MODE_FWD || SHADOW || Ctx::FW_BLK == 1, "one 8-row block per thread: one tile, one sign");
         const int kraw = k0 + 8 * (pt / Ctx::FW_NG);   // 8 k-rows in one hash tile (Z1 % 8 == 0)
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
-        const int e = (kabs / a.Z1) * TN + c.fw_yl + step_shift(step);
-        const int64_t rel = s_off[e] + (int64_t)a.Z2 * (kabs % a.Z1) + c.fw_nin;
+        const int e = tile_div(kabs, a.Z1, p.z1_shift) * TN + c.fw_yl + step_shift(step);
+        const int64_t rel = s_off[e] + (int64_t)a.Z2 * tile_mod(kabs, a.Z1, p.z1_shift) + c.fw_nin;
         r.fw_sgn = s_sgn[e];
 #pragma unroll
         for (int b = 0; b < Ctx::FW_BLK; ++b)
@@ -558,7 +597,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         // this thread's 8-wide chunk of the contraction axis lies in one hash tile (Z2 % 8 == 0)
         const int kraw = k0 + 8 * (pt & 7);
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;   // chunks beyond a ragged contraction length: zeros
-        const int kt = (kabs / a.Z2) * TN + step_shift(step), kin = kabs % a.Z2;
+        const int kt = tile_div(kabs, a.Z2, p.z2_shift) * TN + step_shift(step), kin = tile_mod(kabs, a.Z2, p.z2_shift);
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
           const int e = kt + c.dx_ent[q];
@@ -571,7 +610,7 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
       } else if (MODE == MODE_DX) {
         const int kraw = k0 + 8 * (pt & 7);
         const int kabs = RAGK ? min(kraw, k_end - 8) : kraw;
-        const int kt = (kabs / a.Z2) * TN + step_shift(step), kin = kabs % a.Z2;
+        const int kt = tile_div(kabs, a.Z2, p.z2_shift) * TN + step_shift(step), kin = tile_mod(kabs, a.Z2, p.z2_shift);
         const float keep = (!RAGK || kraw < k_end) ? 1.f : 0.f;
 #pragma unroll
         for (int q = 0; q < Ctx::DX_LOADS; ++q) {
@@ -992,13 +1031,13 @@ __global__ __launch_bounds__((WGM * WGN + 8) * 64) void k_roast_mfma(KernArgs p)
         } else {
           // a lane's four consecutive rows (e % 4) share a hash tile (Z1 % 4 == 0); its column has
           // its own tile column: one table lookup per group of four values
-          const int o = ob + lc, yl = o / a.Z2 - n0 / a.Z2, oin = o % a.Z2;
+          const int o = ob + lc, yl = tile_div(o, a.Z2, p.z2_shift) - tile_div(n0, a.Z2, p.z2_shift), oin = tile_mod(o, a.Z2, p.z2_shift);
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int h = hb + 8 * q + lr;
-            const int ent = (h / a.Z1 - m0 / a.Z1) * TN + yl;
+            const int ent = (tile_div(h, a.Z1, p.z1_shift) - tile_div(m0, a.Z1, p.z1_shift)) * TN + yl;
             const float sc = a.lambda * s_sgn[ent];
-            float* d = p.dM + s_off[ent] + (int64_t)a.Z2 * (h % a.Z1) + oin;
+            float* d = p.dM + s_off[ent] + (int64_t)a.Z2 * tile_mod(h, a.Z1, p.z1_shift) + oin;
 #pragma unroll
             for (int r = 0; r < 4; ++r)
               if (h + r < (int)a.H && o < (int)a.O) unsafeAtomicAdd(d + (int64_t)r * a.Z2, sc * acc[i][j][4 * q + r]);
@@ -1016,6 +1055,9 @@ roast_status launch(KernArgs p, dim3 blocks, hipStream_t s) {
   const int64_t total = (int64_t)blocks.x * blocks.y * blocks.z;
   if (total > (1ll << 30)) return ROAST_ERR_UNSUPPORTED;
   p.nbx = (int)blocks.x; p.nby = (int)blocks.y; p.nbz = (int)blocks.z;
+  auto log2_or_minus1 = [](int z) { int sh = 0; while ((1ll << sh) < (long long)z) ++sh; return (1ll << sh) == (long long)z ? sh : -1; };
+  p.z1_shift = log2_or_minus1(p.a.Z1);
+  p.z2_shift = log2_or_minus1(p.a.Z2);
   const dim3 grid((unsigned)((total + 7) / 8 * 8));
   constexpr int smem = smem_bytes<MODE, BM, BN>();
   static_assert(smem <= 160 * 1024, "LDS budget");
